@@ -1,0 +1,137 @@
+/*
+ * rib_attn.h -- C ABI of the RIB window-attention library for AMD MI355X (gfx950).
+ *
+ * The operator (paper Sec. 2.2 "window-based self-attention"; Sec. 3.1 Eq. 5
+ * "concat + scale" and Eq. 6 "score identity"):
+ *
+ *   A channel-last token grid [B][H][W][C], C = heads*d, channel c = head*d + t,
+ *   is cut into (H/M)*(W/M) windows of M x M tokens after a cyclic shift by s:
+ *   token n = iy*M + ix (row-major) of window (wy, wx) is the grid pixel
+ *       ((wy*M + iy + s) mod H, (wx*M + ix + s) mod W).
+ *   Pixels that wrap around attend freely (no mask).  For every image, window
+ *   and head, with the N = M*M tokens of the window:
+ *
+ *       Q_aug[i] = [ scale_c * q[i]  ||  scale_p * f_q[head][i] ]     (Eq. 5)
+ *       K_aug[j] = [           k[j]  ||            f_k[head][j] ]
+ *       S[i][j]  = < Q_aug[i], K_aug[j] >
+ *                = scale_c * q[i].k[j] + scale_p * f_q[i].f_k[j]       (Eq. 6)
+ *       P        = softmax over j of S,      O[i] = sum_j P[i][j] v[j]
+ *       LSE[i]   = log sum_j exp(S[i][j])    (natural log of the scaled logits)
+ *
+ *   f_q, f_k are the rank-r positional features of RIB; they depend only on the
+ *   position inside the window (Sec. 3.1, last paragraph), so one [heads][N][r]
+ *   table serves every window of every image.  The paper's own scales are
+ *   scale_c = 1/sqrt(d), scale_p = 1/sqrt(r); any pair may be passed.
+ *   S and P are never written to memory and Q_aug / K_aug exist only in
+ *   registers and LDS.  O is returned in ORIGINAL grid coordinates.
+ *
+ * The backward pass is the chain rule through the lines above for a given
+ * upstream gradient dO (the paper trains through the operator, Sec. 4 Table 1,
+ * without printing it):
+ *       dV[j] = sum_i P[i][j] dO[i]          dP[i][j] = dO[i].v[j]
+ *       delta_i = dO[i].O[i]                 dS[i][j] = P[i][j] (dP[i][j] - delta_i)
+ *       dQ[i] = scale_c sum_j dS[i][j] k[j]  dK[j] = scale_c sum_i dS[i][j] q[i]
+ *       dF_q[head][i] = scale_p sum_{images, windows} sum_j dS[i][j] f_k[head][j]
+ *       dF_k[head][j] = scale_p sum_{images, windows} sum_i dS[i][j] f_q[head][i]
+ *
+ * Conventions for every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller, valid on the
+ *     current HIP device.  Unless an entry point says otherwise the library
+ *     allocates nothing, frees nothing and keeps no pointer after returning.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
+ *     is enqueued asynchronously; nothing synchronises.
+ *   - Arguments are validated on the host BEFORE anything is launched; a failed
+ *     validation returns an error code and touches no memory.  No C++ exception
+ *     crosses the boundary.
+ *   - Outputs must not overlap inputs or each other.
+ *   - Entry points are thread-safe (no mutable global state).
+ */
+#ifndef RIB_ATTN_H
+#define RIB_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RIB_OK = 0,
+    RIB_ERR_NULL = 1,        /* a required pointer is NULL */
+    RIB_ERR_SHAPE = 2,       /* non-positive size, H or W not a multiple of window, shift out of range, bad stride */
+    RIB_ERR_DTYPE = 3,       /* dtype is not one of rib_dtype */
+    RIB_ERR_UNSUPPORTED = 4, /* valid problem, but d / r beyond what the kernels are built for */
+    RIB_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than rib_window_attn_bwd_workspace_bytes */
+    RIB_ERR_LAUNCH = 6       /* HIP reported an error when a kernel was enqueued */
+} rib_status;
+
+typedef enum {
+    RIB_F32 = 0,             /* fp32 storage, fp32 arithmetic */
+    RIB_BF16 = 1             /* bf16 storage, bf16 matrix-core operands, fp32 accumulation and softmax state */
+} rib_dtype;
+
+/* Flags for rib_params.flags. */
+enum {
+    /* Always track the running row maximum in the online softmax, even when the
+     * library could prove from vector norms that exp() cannot overflow or
+     * underflow without it.  Results are the same within rounding; this exists
+     * so that both code paths can be tested and timed. */
+    RIB_FLAG_FORCE_ROW_MAX = 1
+};
+
+typedef struct {
+    int32_t B, H, W;         /* grid: images, rows, columns */
+    int32_t heads, d, r;     /* heads, head dim, RIB rank (r may be 0: plain window attention) */
+    int32_t window;          /* M; H % M == 0 and W % M == 0 are required (pad upstream) */
+    int32_t shift;           /* s; 0 <= s < M */
+    float scale_c, scale_p;  /* logit scales of the content and positional parts (Eq. 5) */
+    int32_t dtype;           /* rib_dtype of q, k, v, f_q, f_k, out, d_out, dq, dk, dv */
+    int32_t flags;           /* RIB_FLAG_* */
+    int64_t token_stride;    /* elements between consecutive tokens of q, k and v; 0 means dense (= C).
+                                Lets q, k, v be views into one packed [B][H][W][3C] projection. */
+} rib_params;
+
+/* Built for: 1 <= d <= 64, 0 <= r <= 64, any window side M with M*M <= 65536.
+ * bf16 problems with d <= 32 and d + r <= 64 run on the matrix-core kernels;
+ * everything else runs on a slower fp32 vector-ALU kernel with the same results. */
+
+/* Forward:  out[B][H][W][C]  (dtype of q),  lse[B*nW][heads][N] fp32 or NULL.
+ *   q, k, v : [B][H][W] tokens of C channels, token stride p->token_stride
+ *   f_q,f_k : [heads][N][r], dense; may be NULL iff r == 0
+ *   lse     : window index w = (b*(H/M) + wy)*(W/M) + wx; pass NULL for inference
+ * Returns RIB_OK once the kernels are enqueued on `stream`. */
+rib_status rib_window_attn_fwd(const rib_params *p,
+                               const void *q, const void *k, const void *v,
+                               const void *f_q, const void *f_k,
+                               void *out, float *lse, void *stream);
+
+/* Bytes of device scratch rib_window_attn_bwd needs for this problem (0 if the
+ * parameters are invalid).  The caller allocates it, 256-byte aligned. */
+size_t rib_window_attn_bwd_workspace_bytes(const rib_params *p);
+
+/* Backward.  `out` and `lse` are the results of rib_window_attn_fwd on the same
+ * inputs.  dq, dk, dv [B][H][W][C] (dense, dtype of q) and df_q, df_k
+ * [heads][N][r] fp32 are OVERWRITTEN (df_* are sums over all images and
+ * windows, reduced in a fixed order: results are run-to-run identical).
+ * df_q / df_k may be NULL iff r == 0.  `workspace` is scratch for the duration
+ * of the enqueued work; its contents afterwards are unspecified. */
+rib_status rib_window_attn_bwd(const rib_params *p,
+                               const void *q, const void *k, const void *v,
+                               const void *f_q, const void *f_k,
+                               const void *out, const void *d_out, const float *lse,
+                               void *dq, void *dk, void *dv,
+                               float *df_q, float *df_k,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/* Static, NUL-terminated description of a status code. */
+const char *rib_status_string(rib_status st);
+
+/* Name of the kernel family that would serve this problem ("mfma-bf16",
+ * "valu-f32", ...), or NULL if the parameters are invalid.  For logs and tests. */
+const char *rib_window_attn_kernel_name(const rib_params *p, int backward);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RIB_ATTN_H */

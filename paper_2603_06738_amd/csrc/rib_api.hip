@@ -1,0 +1,105 @@
+// Host side of the C ABI declared in include/rib_attn.h: argument validation,
+// kernel-family selection and launches.  Nothing here allocates device memory or
+// synchronises.
+#include <cmath>
+
+#include "rib_common.h"
+
+namespace rib {
+namespace {
+
+// Validate everything that does not involve data pointers and fill Geo.
+rib_status make_geo(const rib_params *p, Geo *g)
+{
+    if (p == nullptr) return RIB_ERR_NULL;
+    if (p->B <= 0 || p->H <= 0 || p->W <= 0 || p->heads <= 0 || p->d <= 0 || p->r < 0 || p->window <= 0)
+        return RIB_ERR_SHAPE;
+    if (p->H % p->window != 0 || p->W % p->window != 0) return RIB_ERR_SHAPE;
+    if (p->shift < 0 || p->shift >= p->window) return RIB_ERR_SHAPE;
+    const int64_t C = (int64_t)p->heads * p->d;
+    if (p->token_stride != 0 && p->token_stride < C) return RIB_ERR_SHAPE;
+    if (!std::isfinite(p->scale_c) || !std::isfinite(p->scale_p)) return RIB_ERR_SHAPE;
+    if (p->dtype != RIB_F32 && p->dtype != RIB_BF16) return RIB_ERR_DTYPE;
+    if (p->d > 64 || p->r > 64 || (int64_t)p->window * p->window > 65536 || C > (1 << 20))
+        return RIB_ERR_UNSUPPORTED;
+    g->B = p->B; g->H = p->H; g->W = p->W;
+    g->heads = p->heads; g->d = p->d; g->r = p->r;
+    g->M = p->window; g->s = p->shift;
+    g->N = p->window * p->window;
+    g->nwx = p->W / p->window; g->nwy = p->H / p->window;
+    g->C = (int)C;
+    g->tstride = p->token_stride != 0 ? p->token_stride : C;
+    g->scale_c = p->scale_c; g->scale_p = p->scale_p;
+    g->units = (int64_t)p->B * g->nwx * g->nwy * p->heads;
+    // every kernel indexes workgroups with 32-bit block ids and tokens with int
+    const int64_t blocks = g->units * ((g->N + 63) / 64);
+    if (blocks > 0x7fffffffLL || (int64_t)p->B * p->H * p->W > 0x7fffffffLL) return RIB_ERR_UNSUPPORTED;
+    return RIB_OK;
+}
+
+}  // namespace
+}  // namespace rib
+
+using namespace rib;
+
+extern "C" {
+
+const char *rib_status_string(rib_status st)
+{
+    switch (st) {
+    case RIB_OK: return "ok";
+    case RIB_ERR_NULL: return "a required pointer is NULL";
+    case RIB_ERR_SHAPE: return "invalid shape, shift, stride or scale";
+    case RIB_ERR_DTYPE: return "unknown dtype";
+    case RIB_ERR_UNSUPPORTED: return "problem size outside what the kernels are built for";
+    case RIB_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RIB_ERR_LAUNCH: return "HIP kernel launch failed";
+    }
+    return "unknown status";
+}
+
+const char *rib_window_attn_kernel_name(const rib_params *p, int backward)
+{
+    Geo g;
+    if (make_geo(p, &g) != RIB_OK) return nullptr;
+    (void)backward;
+    return "valu-f32";
+}
+
+rib_status rib_window_attn_fwd(const rib_params *p, const void *q, const void *k, const void *v, const void *f_q,
+                               const void *f_k, void *out, float *lse, void *stream)
+{
+    Geo g;
+    rib_status st = make_geo(p, &g);
+    if (st != RIB_OK) return st;
+    if (!q || !k || !v || !out) return RIB_ERR_NULL;
+    if (g.r > 0 && (!f_q || !f_k)) return RIB_ERR_NULL;
+    hipError_t e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out, lse, (hipStream_t)stream);
+    return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
+}
+
+size_t rib_window_attn_bwd_workspace_bytes(const rib_params *p)
+{
+    Geo g;
+    if (make_geo(p, &g) != RIB_OK) return 0;
+    return valu_bwd_workspace(g);
+}
+
+rib_status rib_window_attn_bwd(const rib_params *p, const void *q, const void *k, const void *v, const void *f_q,
+                               const void *f_k, const void *out, const void *d_out, const float *lse, void *dq,
+                               void *dk, void *dv, float *df_q, float *df_k, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    Geo g;
+    rib_status st = make_geo(p, &g);
+    if (st != RIB_OK) return st;
+    if (!q || !k || !v || !out || !d_out || !lse || !dq || !dk || !dv) return RIB_ERR_NULL;
+    if (g.r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < valu_bwd_workspace(g))
+        return RIB_ERR_WORKSPACE;
+    hipError_t e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k,
+                                   workspace, (hipStream_t)stream);
+    return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,64 @@
+// Shared device/host declarations of the RIB window-attention library (gfx950).
+// Internal header: the public interface is include/rib_attn.h.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rib_attn.h"
+
+namespace rib {
+
+// Problem geometry handed to every kernel by value.
+struct Geo {
+    int B, H, W, heads, d, r, M, s;
+    int N;            // M*M tokens per window
+    int nwx, nwy;     // windows per row / column of one image
+    int C;            // heads*d
+    int64_t tstride;  // elements between consecutive tokens of q, k, v
+    float scale_c, scale_p;
+    int64_t units;    // B*nwy*nwx*heads (window, head) pairs
+};
+
+using bf16_t = uint16_t;  // raw bf16 storage
+
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+// Round-to-nearest-even fp32 -> bf16 (NaN kept quiet).
+__device__ __forceinline__ bf16_t narrow_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ void store_as(float *p, float x) { *p = x; }
+__device__ __forceinline__ void store_as(bf16_t *p, float x) { *p = narrow_bf16(x); }
+
+// Sec. 2.2 window partition after a cyclic shift: window-local token n of window
+// w (numbered (b*nwy + wy)*nwx + wx) -> token index (b*H + y)*W + x in the grid.
+__device__ __forceinline__ int64_t grid_token(const Geo &g, int w, int n)
+{
+    int wx = w % g.nwx;
+    int t = w / g.nwx;
+    int wy = t % g.nwy;
+    int b = t / g.nwy;
+    int iy = n / g.M, ix = n - iy * g.M;
+    int y = wy * g.M + iy + g.s;
+    if (y >= g.H) y -= g.H;
+    int x = wx * g.M + ix + g.s;
+    if (x >= g.W) x -= g.W;
+    return ((int64_t)b * g.H + y) * g.W + x;
+}
+
+// Launchers (each returns the hipError_t of its launches).
+hipError_t launch_valu_fwd(const Geo &g, int dtype, const void *q, const void *k, const void *v,
+                           const void *fq, const void *fk, void *out, float *lse, hipStream_t st);
+hipError_t launch_valu_bwd(const Geo &g, int dtype, const void *q, const void *k, const void *v,
+                           const void *fq, const void *fk, const void *out, const void *dout,
+                           const float *lse, void *dq, void *dk, void *dv, float *dfq, float *dfk,
+                           void *ws, hipStream_t st);
+size_t valu_bwd_workspace(const Geo &g);
+
+}  // namespace rib

@@ -1,0 +1,430 @@
+// General-shape RIB window attention on the vector ALU (fp32 arithmetic).
+//
+// Serves fp32 problems and every bf16 problem the matrix-core kernels are not
+// built for (odd head dims, tiny or non-power-of-two windows).  Same operator as
+// include/rib_attn.h describes (paper Sec. 2.2; Sec. 3.1 Eq. 5-6): the augmented
+// vectors Q_aug = [scale_c q || scale_p f_q], K_aug = [k || f_k] are assembled in
+// registers / LDS while the window's tokens are gathered through the cyclic
+// shift, logits are one dot product of the augmented vectors, and the softmax is
+// computed online so no N x N matrix exists anywhere.
+//
+// Thread mapping: a workgroup of 256 lanes owns 64 consecutive window-local rows
+// of one (window, head) unit; 4 neighbouring lanes share a row and split the
+// key (or query) tile between them, merging their partial softmax states with
+// lane shuffles at the end.  K_aug / V tiles of 64 tokens are staged in LDS.
+#include "rib_common.h"
+
+namespace rib {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSplit = 4;                    // lanes per row
+constexpr int kRows = kThreads / kSplit;     // rows per workgroup
+constexpr int kTile = 64;                    // tokens staged per LDS tile
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// Stage one tile of augmented vectors [kTile][DA] (content scaled by sc, RIB part
+// by sp) and optionally a tile of a second grid tensor [kTile][DV] into LDS.
+template <typename T, int DA, int DV>
+__device__ __forceinline__ void stage_tile(const Geo &g, int w, int hd, int j0,
+                                           const T *__restrict__ x, const T *__restrict__ f, float sc, float sp,
+                                           int64_t xstride, const T *__restrict__ y, int64_t ystride,
+                                           float (*A)[DA + 1], float (*Y)[DV + 1], int64_t *tok)
+{
+    const int tid = threadIdx.x;
+    if (tid < kTile) {
+        int j = j0 + tid;
+        tok[tid] = j < g.N ? grid_token(g, w, j) : -1;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < kTile * DA; idx += kThreads) {
+        int jj = idx / DA, t = idx - jj * DA;
+        int64_t tk = tok[jj];
+        float val = 0.f;
+        if (tk >= 0) {
+            if (t < g.d) val = widen(x[tk * xstride + hd * g.d + t]) * sc;
+            else if (t < g.d + g.r) val = widen(f[((int64_t)hd * g.N + (j0 + jj)) * g.r + (t - g.d)]) * sp;
+        }
+        A[jj][t] = val;
+    }
+    if (y != nullptr) {
+        for (int idx = tid; idx < kTile * DV; idx += kThreads) {
+            int jj = idx / DV, t = idx - jj * DV;
+            int64_t tk = tok[jj];
+            float val = 0.f;
+            if (tk >= 0 && t < g.d) val = widen(y[tk * ystride + hd * g.d + t]);
+            Y[jj][t] = val;
+        }
+    }
+}
+
+// This lane's copy of a row's augmented vector.
+template <typename T, int DA>
+__device__ __forceinline__ void load_aug(const Geo &g, int hd, int n, int64_t tk, const T *__restrict__ x,
+                                         const T *__restrict__ f, float sc, float sp, int64_t xstride, float *a)
+{
+#pragma unroll
+    for (int t = 0; t < DA; ++t) {
+        float val = 0.f;
+        if (t < g.d) val = widen(x[tk * xstride + hd * g.d + t]) * sc;
+        else if (t < g.d + g.r) val = widen(f[((int64_t)hd * g.N + n) * g.r + (t - g.d)]) * sp;
+        a[t] = val;
+    }
+}
+
+template <typename T, int DA, int DV>
+__global__ __launch_bounds__(kThreads) void valu_fwd_kernel(Geo g, int nblk, const T *__restrict__ q,
+                                                            const T *__restrict__ k, const T *__restrict__ v,
+                                                            const T *__restrict__ fq, const T *__restrict__ fk,
+                                                            T *__restrict__ out, float *__restrict__ lse)
+{
+    __shared__ float Ks[kTile][DA + 1];
+    __shared__ float Vs[kTile][DV + 1];
+    __shared__ int64_t tok[kTile];
+
+    const int64_t u = blockIdx.x / nblk;
+    const int blk = blockIdx.x - (int)(u * nblk);
+    const int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
+    const int tid = threadIdx.x, row = tid / kSplit, part = tid % kSplit;
+    const int i = blk * kRows + row;
+    const bool live = i < g.N;
+    const int ic = live ? i : g.N - 1;
+    const int64_t tq = grid_token(g, w, ic);
+
+    float qa[DA];
+    load_aug<T, DA>(g, hd, ic, tq, q, fq, g.scale_c * kLog2e, g.scale_p * kLog2e, g.tstride, qa);
+
+    float m = -INFINITY, l = 0.f, o[DV];
+#pragma unroll
+    for (int t = 0; t < DV; ++t) o[t] = 0.f;
+
+    constexpr int KC = 4;  // keys scored before one rescale
+    for (int j0 = 0; j0 < g.N; j0 += kTile) {
+        __syncthreads();
+        stage_tile<T, DA, DV>(g, w, hd, j0, k, fk, 1.f, 1.f, g.tstride, v, g.tstride, Ks, Vs, tok);
+        __syncthreads();
+        for (int c = 0; c < kTile / (kSplit * KC); ++c) {
+            float s[KC], mx = m;
+#pragma unroll
+            for (int e = 0; e < KC; ++e) {
+                int jj = (c * KC + e) * kSplit + part;
+                float acc = 0.f;
+#pragma unroll
+                for (int t = 0; t < DA; ++t) acc = fmaf(qa[t], Ks[jj][t], acc);
+                s[e] = (j0 + jj < g.N) ? acc : -INFINITY;
+                mx = fmaxf(mx, s[e]);
+            }
+            if (mx == -INFINITY) continue;
+            float alpha = exp2f(m - mx);
+            l *= alpha;
+#pragma unroll
+            for (int t = 0; t < DV; ++t) o[t] *= alpha;
+#pragma unroll
+            for (int e = 0; e < KC; ++e) {
+                int jj = (c * KC + e) * kSplit + part;
+                float p = exp2f(s[e] - mx);
+                l += p;
+#pragma unroll
+                for (int t = 0; t < DV; ++t) o[t] = fmaf(p, Vs[jj][t], o[t]);
+            }
+            m = mx;
+        }
+    }
+    // merge the kSplit partial states of this row
+#pragma unroll
+    for (int off = 1; off < kSplit; off <<= 1) {
+        float m2 = __shfl_xor(m, off), l2 = __shfl_xor(l, off);
+        float mx = fmaxf(m, m2);
+        float a = (m == -INFINITY) ? 0.f : exp2f(m - mx);
+        float a2 = (m2 == -INFINITY) ? 0.f : exp2f(m2 - mx);
+        l = l * a + l2 * a2;
+#pragma unroll
+        for (int t = 0; t < DV; ++t) o[t] = o[t] * a + __shfl_xor(o[t], off) * a2;
+        m = mx;
+    }
+    if (!live) return;
+    const float inv = 1.f / l;
+    T *dst = out + tq * g.C + hd * g.d;
+#pragma unroll
+    for (int t = 0; t < DV; ++t)
+        if (t % kSplit == part && t < g.d) store_as(dst + t, o[t] * inv);
+    if (lse != nullptr && part == 0) lse[u * g.N + i] = (m + log2f(l)) * kLn2;
+}
+
+// delta[u][i] = dO[i] . O[i] over the head's channels.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, const T *__restrict__ out,
+                                                              const T *__restrict__ dout, float *__restrict__ delta)
+{
+    int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= g.units * g.N) return;
+    int64_t u = idx / g.N;
+    int n = (int)(idx - u * g.N);
+    int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
+    int64_t base = grid_token(g, w, n) * g.C + hd * g.d;
+    float acc = 0.f;
+    for (int t = 0; t < g.d; ++t) acc = fmaf(widen(out[base + t]), widen(dout[base + t]), acc);
+    delta[idx] = acc;
+}
+
+// dQ and this unit's dF_q contribution: rows are queries, tiles are keys.
+template <typename T, int DA, int DV>
+__global__ __launch_bounds__(kThreads) void valu_bwd_dq_kernel(Geo g, int nblk, const T *__restrict__ q,
+                                                               const T *__restrict__ k, const T *__restrict__ v,
+                                                               const T *__restrict__ fq, const T *__restrict__ fk,
+                                                               const T *__restrict__ dout, const float *__restrict__ lse,
+                                                               const float *__restrict__ delta, T *__restrict__ dq,
+                                                               float *__restrict__ dfq_part)
+{
+    __shared__ float Ks[kTile][DA + 1];
+    __shared__ float Vs[kTile][DV + 1];
+    __shared__ int64_t tok[kTile];
+
+    const int64_t u = blockIdx.x / nblk;
+    const int blk = blockIdx.x - (int)(u * nblk);
+    const int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
+    const int tid = threadIdx.x, row = tid / kSplit, part = tid % kSplit;
+    const int i = blk * kRows + row;
+    const bool live = i < g.N;
+    const int ic = live ? i : g.N - 1;
+    const int64_t tq = grid_token(g, w, ic);
+
+    float qa[DA], go[DV], acc[DA];
+    load_aug<T, DA>(g, hd, ic, tq, q, fq, g.scale_c * kLog2e, g.scale_p * kLog2e, g.tstride, qa);
+#pragma unroll
+    for (int t = 0; t < DV; ++t) go[t] = t < g.d ? widen(dout[tq * g.C + hd * g.d + t]) : 0.f;
+#pragma unroll
+    for (int t = 0; t < DA; ++t) acc[t] = 0.f;
+    const float lse2 = lse[u * g.N + ic] * kLog2e;
+    const float dl = delta[u * g.N + ic];
+
+    for (int j0 = 0; j0 < g.N; j0 += kTile) {
+        __syncthreads();
+        stage_tile<T, DA, DV>(g, w, hd, j0, k, fk, 1.f, 1.f, g.tstride, v, g.tstride, Ks, Vs, tok);
+        __syncthreads();
+        for (int jj = part; jj < kTile; jj += kSplit) {
+            if (j0 + jj >= g.N) break;
+            float s = 0.f, dp = 0.f;
+#pragma unroll
+            for (int t = 0; t < DA; ++t) s = fmaf(qa[t], Ks[jj][t], s);
+#pragma unroll
+            for (int t = 0; t < DV; ++t) dp = fmaf(go[t], Vs[jj][t], dp);
+            float ds = exp2f(s - lse2) * (dp - dl);
+#pragma unroll
+            for (int t = 0; t < DA; ++t) acc[t] = fmaf(ds, Ks[jj][t], acc[t]);
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < kSplit; off <<= 1)
+#pragma unroll
+        for (int t = 0; t < DA; ++t) acc[t] += __shfl_xor(acc[t], off);
+    if (!live) return;
+    T *dst = dq + tq * g.C + hd * g.d;
+    float *fdst = dfq_part + (u * g.N + i) * g.r;
+#pragma unroll
+    for (int t = 0; t < DA; ++t) {
+        if (t % kSplit != part) continue;
+        if (t < g.d) store_as(dst + t, acc[t] * g.scale_c);
+        else if (t < g.d + g.r) fdst[t - g.d] = acc[t] * g.scale_p;
+    }
+}
+
+// dK, dV and this unit's dF_k contribution: rows are keys, tiles are queries.
+template <typename T, int DA, int DV>
+__global__ __launch_bounds__(kThreads) void valu_bwd_dkv_kernel(Geo g, int nblk, const T *__restrict__ q,
+                                                                const T *__restrict__ k, const T *__restrict__ v,
+                                                                const T *__restrict__ fq, const T *__restrict__ fk,
+                                                                const T *__restrict__ dout, const float *__restrict__ lse,
+                                                                const float *__restrict__ delta, T *__restrict__ dk,
+                                                                T *__restrict__ dv, float *__restrict__ dfk_part)
+{
+    __shared__ float Qs[kTile][DA + 1];
+    __shared__ float Gs[kTile][DV + 1];
+    __shared__ float lse2s[kTile], dls[kTile];
+    __shared__ int64_t tok[kTile];
+
+    const int64_t u = blockIdx.x / nblk;
+    const int blk = blockIdx.x - (int)(u * nblk);
+    const int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
+    const int tid = threadIdx.x, row = tid / kSplit, part = tid % kSplit;
+    const int j = blk * kRows + row;
+    const bool live = j < g.N;
+    const int jc = live ? j : g.N - 1;
+    const int64_t tkv = grid_token(g, w, jc);
+
+    float ka[DA], va[DV], dka[DA], dva[DV];
+    load_aug<T, DA>(g, hd, jc, tkv, k, fk, 1.f, 1.f, g.tstride, ka);
+#pragma unroll
+    for (int t = 0; t < DV; ++t) va[t] = t < g.d ? widen(v[tkv * g.tstride + hd * g.d + t]) : 0.f;
+#pragma unroll
+    for (int t = 0; t < DA; ++t) dka[t] = 0.f;
+#pragma unroll
+    for (int t = 0; t < DV; ++t) dva[t] = 0.f;
+
+    for (int i0 = 0; i0 < g.N; i0 += kTile) {
+        __syncthreads();
+        stage_tile<T, DA, DV>(g, w, hd, i0, q, fq, g.scale_c, g.scale_p, g.tstride, dout, (int64_t)g.C, Qs, Gs, tok);
+        if (tid < kTile) {
+            int i = i0 + tid;
+            lse2s[tid] = i < g.N ? lse[u * g.N + i] * kLog2e : 0.f;
+            dls[tid] = i < g.N ? delta[u * g.N + i] : 0.f;
+        }
+        __syncthreads();
+        for (int ii = part; ii < kTile; ii += kSplit) {
+            if (i0 + ii >= g.N) break;
+            float s = 0.f, dp = 0.f;
+#pragma unroll
+            for (int t = 0; t < DA; ++t) s = fmaf(ka[t], Qs[ii][t], s);
+#pragma unroll
+            for (int t = 0; t < DV; ++t) dp = fmaf(va[t], Gs[ii][t], dp);
+            float p = exp2f(s * kLog2e - lse2s[ii]);
+            float ds = p * (dp - dls[ii]);
+#pragma unroll
+            for (int t = 0; t < DV; ++t) dva[t] = fmaf(p, Gs[ii][t], dva[t]);
+#pragma unroll
+            for (int t = 0; t < DA; ++t) dka[t] = fmaf(ds, Qs[ii][t], dka[t]);
+        }
+    }
+#pragma unroll
+    for (int off = 1; off < kSplit; off <<= 1) {
+#pragma unroll
+        for (int t = 0; t < DA; ++t) dka[t] += __shfl_xor(dka[t], off);
+#pragma unroll
+        for (int t = 0; t < DV; ++t) dva[t] += __shfl_xor(dva[t], off);
+    }
+    if (!live) return;
+    T *kdst = dk + tkv * g.C + hd * g.d;
+    T *vdst = dv + tkv * g.C + hd * g.d;
+    float *fdst = dfk_part + (u * g.N + j) * g.r;
+#pragma unroll
+    for (int t = 0; t < DA; ++t) {
+        if (t % kSplit != part) continue;
+        if (t < g.d) store_as(kdst + t, dka[t]);
+        else if (t < g.d + g.r) fdst[t - g.d] = dka[t];
+    }
+#pragma unroll
+    for (int t = 0; t < DV; ++t)
+        if (t % kSplit == part && t < g.d) store_as(vdst + t, dva[t]);
+}
+
+// dF[hd][e] = sum over windows w (ascending) of part[(w*heads + hd)][e]; e over N*r.
+__global__ __launch_bounds__(kThreads) void reduce_df_kernel(Geo g, const float *__restrict__ part_q,
+                                                             const float *__restrict__ part_k,
+                                                             float *__restrict__ dfq, float *__restrict__ dfk)
+{
+    const int64_t per_head = (int64_t)g.N * g.r;
+    int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= per_head * g.heads) return;
+    int hd = (int)(idx / per_head);
+    int64_t e = idx - hd * per_head;
+    const float *src = blockIdx.y == 0 ? part_q : part_k;
+    float *dst = blockIdx.y == 0 ? dfq : dfk;
+    const int64_t nwin = g.units / g.heads;
+    float acc = 0.f;
+    for (int64_t w = 0; w < nwin; ++w) acc += src[(w * g.heads + hd) * per_head + e];
+    dst[idx] = acc;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct BwdWs {
+    size_t delta_off, dfq_off, dfk_off, total;
+};
+inline BwdWs ws_layout(const Geo &g)
+{
+    BwdWs l;
+    size_t rows = (size_t)g.units * g.N;
+    l.delta_off = 0;
+    l.dfq_off = align256(rows * sizeof(float));
+    l.dfk_off = l.dfq_off + align256(rows * g.r * sizeof(float));
+    l.total = l.dfk_off + align256(rows * g.r * sizeof(float));
+    return l;
+}
+
+template <typename T, int DA, int DV>
+hipError_t fwd_t(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
+                 void *out, float *lse, hipStream_t st)
+{
+    int nblk = (g.N + kRows - 1) / kRows;
+    dim3 grid((unsigned)(g.units * nblk));
+    hipLaunchKernelGGL((valu_fwd_kernel<T, DA, DV>), grid, dim3(kThreads), 0, st, g, nblk, (const T *)q,
+                       (const T *)k, (const T *)v, (const T *)fq, (const T *)fk, (T *)out, lse);
+    return hipGetLastError();
+}
+
+template <typename T, int DA, int DV>
+hipError_t bwd_t(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
+                 const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv, float *dfq,
+                 float *dfk, void *ws, hipStream_t st)
+{
+    BwdWs l = ws_layout(g);
+    float *delta = (float *)((char *)ws + l.delta_off);
+    float *pq = (float *)((char *)ws + l.dfq_off);
+    float *pk = (float *)((char *)ws + l.dfk_off);
+    int64_t rows = g.units * g.N;
+    hipLaunchKernelGGL((valu_delta_kernel<T>), dim3((unsigned)((rows + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       st, g, (const T *)out, (const T *)dout, delta);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    int nblk = (g.N + kRows - 1) / kRows;
+    dim3 grid((unsigned)(g.units * nblk));
+    hipLaunchKernelGGL((valu_bwd_dq_kernel<T, DA, DV>), grid, dim3(kThreads), 0, st, g, nblk, (const T *)q,
+                       (const T *)k, (const T *)v, (const T *)fq, (const T *)fk, (const T *)dout, lse, delta, (T *)dq,
+                       pq);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((valu_bwd_dkv_kernel<T, DA, DV>), grid, dim3(kThreads), 0, st, g, nblk, (const T *)q,
+                       (const T *)k, (const T *)v, (const T *)fq, (const T *)fk, (const T *)dout, lse, delta, (T *)dk,
+                       (T *)dv, pk);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (g.r > 0) {
+        int64_t n = (int64_t)g.heads * g.N * g.r;
+        hipLaunchKernelGGL(reduce_df_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads), 2), dim3(kThreads), 0, st,
+                           g, pq, pk, dfq, dfk);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+// Smallest compiled (DA, DV) bucket holding d + r and d.
+inline int bucket(const Geo &g)
+{
+    int da = g.d + g.r;
+    if (da <= 16 && g.d <= 8) return 0;
+    if (da <= 48 && g.d <= 32) return 1;
+    if (da <= 64 && g.d <= 32) return 2;
+    return 3;  // da <= 128, d <= 64 (checked by the caller)
+}
+
+}  // namespace
+
+size_t valu_bwd_workspace(const Geo &g) { return ws_layout(g).total; }
+
+#define RIB_VALU_DISPATCH(FN, ...)                                                         \
+    switch (bucket(g) * 2 + (dtype == RIB_BF16 ? 1 : 0)) {                                 \
+    case 0: return FN<float, 16, 8>(__VA_ARGS__);                                          \
+    case 1: return FN<bf16_t, 16, 8>(__VA_ARGS__);                                         \
+    case 2: return FN<float, 48, 32>(__VA_ARGS__);                                         \
+    case 3: return FN<bf16_t, 48, 32>(__VA_ARGS__);                                        \
+    case 4: return FN<float, 64, 32>(__VA_ARGS__);                                         \
+    case 5: return FN<bf16_t, 64, 32>(__VA_ARGS__);                                        \
+    case 6: return FN<float, 128, 64>(__VA_ARGS__);                                        \
+    default: return FN<bf16_t, 128, 64>(__VA_ARGS__);                                      \
+    }
+
+hipError_t launch_valu_fwd(const Geo &g, int dtype, const void *q, const void *k, const void *v, const void *fq,
+                           const void *fk, void *out, float *lse, hipStream_t st)
+{
+    RIB_VALU_DISPATCH(fwd_t, g, q, k, v, fq, fk, out, lse, st)
+}
+
+hipError_t launch_valu_bwd(const Geo &g, int dtype, const void *q, const void *k, const void *v, const void *fq,
+                           const void *fk, const void *out, const void *dout, const float *lse, void *dq, void *dk,
+                           void *dv, float *dfq, float *dfk, void *ws, hipStream_t st)
+{
+    RIB_VALU_DISPATCH(bwd_t, g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st)
+}
+
+}  // namespace rib

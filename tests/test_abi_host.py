@@ -1,0 +1,99 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the public header declares, and rejects bad arguments with the
+documented status codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_06738_amd import binding as rb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x1000  # non-NULL dummy "device pointer"; validation must fail before it is ever used
+
+
+def good(**kw):
+    base = dict(B=2, H=8, W=8, heads=2, d=4, r=2, window=4, shift=1, scale_c=0.5, scale_p=0.5,
+                dtype="f32")
+    base.update(kw)
+    return rb.make_params(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "rib_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(rib_[a-z_]+)\s*\(", text))
+    assert declared == set(rb.EXPORTS)
+    lib = rb.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_params_struct_layout_matches_header():
+    # 8 int32 + 2 float + 2 int32 + int64, naturally aligned
+    assert ctypes.sizeof(rb.RibParams) == 56
+    assert rb.RibParams.token_stride.offset == 48
+
+
+def test_status_strings():
+    seen = {rb.status_string(i) for i in range(7)}
+    assert len(seen) == 7 and all(seen)
+
+
+def fwd_status(p, **ptrs):
+    a = dict(q=FAKE, k=FAKE, v=FAKE, f_q=FAKE, f_k=FAKE, out=FAKE, lse=None)
+    a.update(ptrs)
+    return rb.rib_window_attn_fwd_status(p, a["q"], a["k"], a["v"], a["f_q"], a["f_k"], a["out"], a["lse"], stream=0)
+
+
+@pytest.mark.parametrize("kw", [dict(B=0), dict(H=-8), dict(d=0), dict(r=-1), dict(window=0),
+                                dict(H=10), dict(W=6), dict(shift=4), dict(shift=-1),
+                                dict(token_stride=7), dict(scale_c=float("nan"))])
+def test_shape_errors(kw):
+    assert fwd_status(good(**kw)) == 2
+    assert rb.rib_window_attn_bwd_workspace_bytes(good(**kw)) == 0
+    assert rb.kernel_name(good(**kw)) is None
+
+
+def test_dtype_and_unsupported_errors():
+    assert fwd_status(good(dtype=7)) == 3
+    assert fwd_status(good(d=65)) == 4
+    assert fwd_status(good(r=65)) == 4
+    assert fwd_status(good(H=512, W=512, window=512)) == 4
+
+
+def test_null_pointer_errors():
+    assert rb.rib_window_attn_fwd_status(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, stream=0) == 1
+    for name in ("q", "k", "v", "out", "f_q", "f_k"):
+        assert fwd_status(good(), **{name: None}) == 1
+    # r == 0 makes the RIB tables optional: validation passes and only the launch
+    # fails (no GPU here) or succeeds (on a GPU machine this test is not given real memory)
+    p0 = good(r=0, B=1, H=4, W=4)
+    assert rb.kernel_name(p0) is not None
+
+
+def test_backward_workspace_validation():
+    p = good()
+    need = rb.rib_window_attn_bwd_workspace_bytes(p)
+    assert need > 0 and need % 256 == 0
+    args = [FAKE] * 13
+
+    def call(ws, nbytes, **kw):
+        a = list(args)
+        for i, n in enumerate(("q", "k", "v", "f_q", "f_k", "out", "d_out", "lse", "dq", "dk", "dv", "df_q", "df_k")):
+            if n in kw:
+                a[i] = kw[n]
+        return rb.rib_window_attn_bwd_status(p, *a, ws, nbytes, stream=0)
+
+    assert call(None, need) == 5
+    assert call(0x1000, need - 1) == 5
+    assert call(0x1010, need) == 5          # not 256-byte aligned
+    assert call(0x1000, need, lse=None) == 1
+    assert call(0x1000, need, df_q=None) == 1
+    assert call(0x1000, need, d_out=None) == 1
+
+
+def test_kernel_family_names():
+    assert rb.kernel_name(good()) is not None
+    assert rb.kernel_name(good(), backward=True) is not None

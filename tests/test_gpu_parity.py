@@ -1,0 +1,159 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU
+oracle on the same seeded inputs, element by element.
+
+Tolerances (max abs error per output tensor): 1e-4 for fp32 problems, 2e-2 for
+bf16 storage with fp32 accumulation; the same bounds for gradients and LSE."""
+import math
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from paper_2603_06738_amd import binding as rb
+from paper_2603_06738_amd import workloads as wk
+from helpers import geometry
+
+FORCE_MAX = rb.RIB_FLAG_FORCE_ROW_MAX
+
+
+def _small_cases():
+    c = wk.custom
+    cases = []
+    for dt in ("f32", "bf16"):
+        cases += [
+            c(f"m1-{dt}", dt, 2, 3, 5, 2, 3, 2, 1, 0, 201),                 # one token per window
+            c(f"m2-{dt}", dt, 2, 4, 6, 2, 3, 2, 2, 1, 202),
+            c(f"m3-{dt}", dt, 1, 6, 9, 3, 7, 3, 3, 2, 203),                 # odd everything
+            c(f"m5-{dt}", dt, 1, 10, 5, 2, 30, 16, 5, 4, 204),
+            c(f"m9-{dt}", dt, 1, 9, 18, 2, 30, 8, 9, 3, 205),               # N=81: one tile + ragged tail
+            c(f"m12-{dt}", dt, 1, 24, 12, 2, 30, 16, 12, 7, 206),           # N=144
+            c(f"m16-{dt}", dt, 2, 16, 32, 3, 30, 16, 16, 8, 207),           # N=256, paper-like head
+            c(f"norib-{dt}", dt, 1, 8, 8, 2, 16, 0, 8, 3, 208),             # r = 0
+            c(f"wide-{dt}", dt, 1, 8, 8, 1, 64, 64, 8, 0, 209),             # largest d and r
+            c(f"eq5-{dt}", dt, 1, 16, 16, 6, 30, 18, 16, 5, 210,
+              scale_c=1 / math.sqrt(30), scale_p=1 / math.sqrt(18)),        # the paper's scales and an SST rank
+            c(f"d32r16-{dt}", dt, 1, 32, 32, 2, 32, 16, 32, 16, 211),       # SST-L head, N=1024
+            c(f"d30r34-{dt}", dt, 1, 16, 16, 2, 30, 34, 16, 1, 212),        # SST second-cycle rank
+        ]
+    return cases
+
+
+SMALL = _small_cases()
+
+
+def _check_fwd(oracle, gh, wl, x, flags=0, packed=False):
+    g = geometry(oracle, wl)
+    O_ref, lse_ref = oracle.fwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"])
+    t = gh.device_inputs(wl, x, packed=packed)
+    out, lse = gh.gpu_fwd(wl, t, flags=flags, packed=packed)
+    tol = gh.TOL[wl.dtype]
+    assert gh.max_abs(gh.host(out), O_ref) <= tol
+    assert gh.max_abs(gh.host(lse), lse_ref) <= tol
+    return t, out, lse
+
+
+@pytest.fixture(scope="module")
+def gh():
+    import gpu_helpers
+    return gpu_helpers
+
+
+@pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
+@pytest.mark.parametrize("flags", [0, FORCE_MAX], ids=["auto", "rowmax"])
+def test_forward_small(oracle, gh, wl, flags):
+    _check_fwd(oracle, gh, wl, wk.make_inputs(wl), flags=flags)
+
+
+@pytest.mark.parametrize("wl", SMALL, ids=lambda w: w.name)
+def test_backward_small(oracle, gh, wl):
+    x = wk.make_inputs(wl, with_dout=True)
+    t, out, lse = _check_fwd(oracle, gh, wl, x)
+    got = gh.gpu_bwd(wl, t, out, lse)
+    ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    tol = gh.TOL[wl.dtype]
+    for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+        assert gh.max_abs(gh.host(a), b) <= tol, name
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_forward_full_configs(oracle, gh, name):
+    """Configs 1 and 2 end to end (every output element)."""
+    wl = wk.WORKLOADS[name]
+    _check_fwd(oracle, gh, wl, wk.make_inputs(wl))
+
+
+def test_packed_qkv_stride(oracle, gh):
+    """q, k, v as strided views of one [B,H,W,3C] buffer (token_stride = 3C)."""
+    for dt in ("f32", "bf16"):
+        wl = wk.custom(f"packed-{dt}", dt, 1, 16, 16, 2, 30, 16, 16, 3, 221, backward=True)
+        x = wk.make_inputs(wl)
+        t, out, lse = _check_fwd(oracle, gh, wl, x, packed=True)
+        got = gh.gpu_bwd(wl, t, out, lse, packed=True)
+        ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+        for a, b in zip(got, ref):
+            assert gh.max_abs(gh.host(a), b) <= gh.TOL[dt]
+
+
+def test_inference_without_lse(oracle, gh):
+    wl = wk.custom("nolse", "bf16", 1, 16, 16, 2, 30, 16, 16, 0, 222)
+    x = wk.make_inputs(wl)
+    O_ref, _ = oracle.fwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"])
+    out, _ = gh.gpu_fwd(wl, gh.device_inputs(wl, x), want_lse=False)
+    assert gh.max_abs(gh.host(out), O_ref) <= gh.TOL["bf16"]
+
+
+def test_large_logits_need_the_row_max(oracle, gh):
+    """Logits of magnitude ~1e2..1e3: exp() without a running maximum would
+    overflow, so the library must fall back to max tracking on its own."""
+    for dt in ("f32", "bf16"):
+        wl = wk.custom(f"big-{dt}", dt, 1, 16, 16, 2, 30, 16, 16, 4, 223, scale_c=4.0, scale_p=6.0,
+                       backward=True)
+        x = wk.make_inputs(wl)
+        t, out, lse = _check_fwd(oracle, gh, wl, x)
+        got = gh.gpu_bwd(wl, t, out, lse)
+        ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+        for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+            scale = max(1.0, float(np.abs(b).max()))
+            assert gh.max_abs(gh.host(a), b) <= gh.TOL[dt] * scale, name
+
+
+SAMPLED = {"c3": 6, "c3s": 6, "c4": 4, "c5": 6}
+
+
+@pytest.mark.parametrize("name", list(SAMPLED))
+@pytest.mark.parametrize("flags", [0, FORCE_MAX], ids=["auto", "rowmax"])
+def test_forward_full_size_sampled_units(oracle, gh, name, flags):
+    """Configs 3-5 at full size in the launch configuration the benchmark times;
+    the oracle recomputes a seeded sample of (window, head) units, first and
+    last unit included."""
+    wl = wk.WORKLOADS[name]
+    x = wk.make_inputs(wl, with_dout=False)
+    g = geometry(oracle, wl)
+    rng = np.random.default_rng(wl.seed)
+    units = sorted({0, wl.n_units - 1, *rng.choice(wl.n_units, SAMPLED[name] - 2, replace=False).tolist()})
+    O_ref, lse_ref = oracle.fwd_units(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], units)
+    t = gh.device_inputs(wl, x)
+    out, lse = gh.gpu_fwd(wl, t, flags=flags)
+    out_h, lse_h = gh.host(out), gh.host(lse)
+    assert np.isfinite(out_h).all() and np.isfinite(lse_h).all()
+    for a, u in enumerate(units):
+        assert gh.max_abs(gh.gather_unit(oracle, g, out_h, u), O_ref[a]) <= gh.TOL[wl.dtype], u
+        assert gh.max_abs(lse_h[u // wl.heads, u % wl.heads], lse_ref[a]) <= gh.TOL[wl.dtype], u
+
+
+def test_config5_backward_full_size(oracle, gh):
+    """Config 5 (training step) at full size: dQ, dK, dV on sampled units and the
+    RIB gradients dF_q, dF_k -- sums over all 144 windows -- on every element
+    (the oracle runs the whole backward once for those)."""
+    wl = wk.WORKLOADS["c5"]
+    x = wk.make_inputs(wl)
+    g = geometry(oracle, wl)
+    t = gh.device_inputs(wl, x)
+    out, lse = gh.gpu_fwd(wl, t)
+    got = [gh.host(a) for a in gh.gpu_bwd(wl, t, out, lse)]
+    print("config 5: oracle backward on", oracle.num_threads(), "threads ...", flush=True)
+    ref = oracle.bwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    tol = gh.TOL[wl.dtype]
+    for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+        assert gh.max_abs(a, b) <= tol, name

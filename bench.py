@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Benchmark of the RIB window-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5] [--all]
+
+One "step" is one pass of the whole hot path over one batch of synthetic input:
+forward (gather + RIB concat + scores + online softmax + PV + scatter) followed,
+for the training workload, by the backward pass (delta, dQ/dK/dV, RIB gradient
+reduction).  The default workload is config 5 of the benchmark spec (fwd+bwd, bf16,
+B=16, 96x96 grid, 32x32 windows, shift 16).  Inputs are resident in HBM before
+the timed region starts.  Prints ONE JSON line.
+
+`--all` adds a `configs` table with forward numbers for every named workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, vendor figure
+PEAK_F32_VALU_TFLOPS = 157.3  # MI355X fp32 vector, vendor figure
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c5")
+    ap.add_argument("--all", action="store_true", help="also time the forward of every named workload")
+    ap.add_argument("--force-row-max", action="store_true", help="time the max-tracking softmax path")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=0, help="units in the CPU-oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+class Runner:
+    """Device buffers of one workload plus closures that enqueue fwd / bwd."""
+
+    def __init__(self, wl, flags=0):
+        import torch
+        from paper_2603_06738_amd import binding as rb
+        from paper_2603_06738_amd import workloads as wk
+        self.wl, self.rb, self.torch = wl, rb, torch
+        x = wk.make_inputs(wl, with_dout=wl.backward)
+        self.t = {n: rb.to_device(a, wl.dtype) for n, a in x.items()}
+        del x
+        td = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        dev = "cuda:0"
+        grid = (wl.B, wl.H, wl.W, wl.C)
+        self.p = rb.params_of(wl, flags=flags)
+        self.out = torch.empty(grid, dtype=td, device=dev)
+        self.lse = torch.empty((wl.n_windows, wl.heads, wl.N), dtype=torch.float32, device=dev)
+        if wl.backward:
+            self.dq, self.dk, self.dv = (torch.empty(grid, dtype=td, device=dev) for _ in range(3))
+            self.dfq, self.dfk = (torch.empty((wl.heads, wl.N, wl.r), dtype=torch.float32, device=dev)
+                                  for _ in range(2))
+            self.ws = rb.alloc_workspace(self.p)
+
+    def fwd(self):
+        t = self.t
+        self.rb.rib_window_attn_fwd(self.p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], self.out, self.lse)
+
+    def bwd(self):
+        t = self.t
+        self.rb.rib_window_attn_bwd(self.p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], self.out, t["d_out"],
+                                    self.lse, self.dq, self.dk, self.dv, self.dfq, self.dfk, self.ws)
+
+
+def time_steps(r, steps, warmup):
+    """Returns (wall ms per step, mean fwd ms, mean bwd ms) with HIP events on the launch stream."""
+    torch = r.torch
+    for _ in range(warmup):
+        r.fwd()
+        if r.wl.backward:
+            r.bwd()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ev[s][0].record()
+        r.fwd()
+        ev[s][1].record()
+        if r.wl.backward:
+            r.bwd()
+        ev[s][2].record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    fwd = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    bwd = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    return wall, fwd, bwd
+
+
+def cpu_baseline(wl, n_units):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2603_06738_amd import workloads as wk
+    g = oracle.Geometry(wl.B, wl.H, wl.W, wl.heads, wl.d, wl.r, wl.M, wl.s, wl.scale_c, wl.scale_p)
+    x = wk.make_inputs(wl, with_dout=wl.backward)
+    units = np.linspace(0, wl.n_units - 1, n_units).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.fwd_units(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], units)
+    if wl.backward:
+        oracle.bwd_units(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"], units)
+    dt = time.perf_counter() - t0
+    flop = (wl.fwd_flop + (wl.bwd_flop if wl.backward else 0.0)) * n_units / wl.n_units
+    return {"value": flop / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds": round(dt, 3),
+            "sample": f"{n_units} of {wl.n_units} (window, head) units of {wl.name}, "
+                      f"{'fwd+bwd' if wl.backward else 'fwd'}, fp64"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives are part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_06738_amd import binding as rb
+    from paper_2603_06738_amd import workloads as wk
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    rb.load()
+    wl = wk.WORKLOADS[a.workload]
+    flags = rb.RIB_FLAG_FORCE_ROW_MAX if a.force_row_max else 0
+
+    r = Runner(wl, flags)
+    wall, fwd_ms, bwd_ms = time_steps(r, a.steps, a.warmup)
+    step_flop = wl.fwd_flop + (wl.bwd_flop if wl.backward else 0.0)
+    value = step_flop / (wall * 1e-3) / 1e12
+
+    fwd_tflops = wl.fwd_flop / (fwd_ms * 1e-3) / 1e12
+    res = {
+        "metric": "RIB window-attention TFLOP/s fwd(+bwd) at 32x32 windows",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(wall, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {'fwd+bwd' if wl.backward else 'fwd'} {wl.dtype} "
+                               f"B={wl.B} H=W={wl.H} C={wl.C} heads={wl.heads} d={wl.d} r={wl.r} "
+                               f"window={wl.M} shift={wl.s}",
+                   "softmax_path": "row-max" if a.force_row_max else "auto",
+                   "kernels": {"fwd": rb.kernel_name(r.p, False), "bwd": rb.kernel_name(r.p, True)}},
+        "tokens_per_s": round(wl.tokens / (wall * 1e-3), 1),
+        "fwd_ms": round(fwd_ms, 4), "fwd_tflops": round(fwd_tflops, 2),
+        "fwd_pct_bf16_peak": round(100 * fwd_tflops / PEAK_BF16_TFLOPS, 2),
+    }
+    if wl.backward:
+        bwd_tflops = wl.bwd_flop / (bwd_ms * 1e-3) / 1e12
+        res.update(bwd_ms=round(bwd_ms, 4), bwd_tflops=round(bwd_tflops, 2),
+                   bwd_pct_bf16_peak=round(100 * bwd_tflops / PEAK_BF16_TFLOPS, 2))
+    # roofline of the forward kernel (one launch per step; algorithmic flop of the unpadded dims)
+    mfma = rb.kernel_name(r.p, False) == "mfma-bf16"
+    peak = PEAK_BF16_TFLOPS if mfma else PEAK_F32_VALU_TFLOPS
+    res["roofline"] = {"kernel": "forward (" + rb.kernel_name(r.p, False) + ")",
+                       "bound": "mfma" if mfma else "alu", "achieved": round(fwd_tflops, 2), "peak": peak,
+                       "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4), "traffic": None}
+    if wl.backward:
+        bmfma = rb.kernel_name(r.p, True) == "mfma-bf16"
+        bpeak = PEAK_BF16_TFLOPS if bmfma else PEAK_F32_VALU_TFLOPS
+        res["roofline_bwd"] = {"kernel": "backward (" + rb.kernel_name(r.p, True) + ", all its launches)",
+                               "bound": "mfma" if bmfma else "alu", "achieved": round(bwd_tflops, 2),
+                               "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4),
+                               "traffic": None}
+    del r
+    torch.cuda.empty_cache()
+
+    if a.all:
+        table = {}
+        for name, w2 in wk.WORKLOADS.items():
+            r2 = Runner(w2.__class__(**{**w2.__dict__, "backward": False}), flags)
+            _, f_ms, _ = time_steps(r2, max(10, a.steps), a.warmup)
+            tf = w2.fwd_flop / (f_ms * 1e-3) / 1e12
+            pk = PEAK_BF16_TFLOPS if rb.kernel_name(r2.p, False) == "mfma-bf16" else PEAK_F32_VALU_TFLOPS
+            table[name] = {"fwd_ms": round(f_ms, 4), "fwd_tflops": round(tf, 2),
+                           "tokens_per_s": round(w2.tokens / (f_ms * 1e-3), 1),
+                           "frac_of_peak": round(tf / pk, 4), "peak_tflops": pk,
+                           "hbm_gbs": round(w2.fwd_bytes / (f_ms * 1e-3) / 1e9, 1),
+                           "kernel": rb.kernel_name(r2.p, False)}
+            del r2
+            torch.cuda.empty_cache()
+        res["configs"] = table
+
+    if not a.no_cpu_baseline:
+        n_units = a.cpu_units or min(wl.n_units, 864)
+        res["cpu_baseline"] = cpu_baseline(wl, n_units)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

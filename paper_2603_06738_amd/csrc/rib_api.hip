@@ -62,7 +62,7 @@ const char *rib_window_attn_kernel_name(const rib_params *p, int backward)
 {
     Geo g;
     if (make_geo(p, &g) != RIB_OK) return nullptr;
-    (void)backward;
+    if (!backward && mfma_fwd_supported(g, p->dtype)) return "mfma-bf16";
     return "valu-f32";
 }
 
@@ -74,7 +74,12 @@ rib_status rib_window_attn_fwd(const rib_params *p, const void *q, const void *k
     if (st != RIB_OK) return st;
     if (!q || !k || !v || !out) return RIB_ERR_NULL;
     if (g.r > 0 && (!f_q || !f_k)) return RIB_ERR_NULL;
-    hipError_t e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out, lse, (hipStream_t)stream);
+    hipError_t e;
+    if (mfma_fwd_supported(g, p->dtype))
+        e = launch_mfma_fwd(g, (p->flags & RIB_FLAG_FORCE_ROW_MAX) != 0, q, k, v, f_q, f_k, out, lse,
+                            (hipStream_t)stream);
+    else
+        e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out, lse, (hipStream_t)stream);
     return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
 }
 

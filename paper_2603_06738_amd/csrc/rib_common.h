@@ -61,4 +61,9 @@ hipError_t launch_valu_bwd(const Geo &g, int dtype, const void *q, const void *k
                            void *ws, hipStream_t st);
 size_t valu_bwd_workspace(const Geo &g);
 
+// Matrix-core forward (bf16): whether it serves this problem, and its launcher.
+bool mfma_fwd_supported(const Geo &g, int dtype);
+hipError_t launch_mfma_fwd(const Geo &g, int force_max, const void *q, const void *k, const void *v,
+                           const void *fq, const void *fk, void *out, float *lse, hipStream_t st);
+
 }  // namespace rib

@@ -63,6 +63,7 @@ const char *rib_window_attn_kernel_name(const rib_params *p, int backward)
     Geo g;
     if (make_geo(p, &g) != RIB_OK) return nullptr;
     if (!backward && mfma_fwd_supported(g, p->dtype)) return "mfma-bf16";
+    if (backward && mfma_bwd_supported(g, p->dtype)) return "mfma-bf16";
     return "valu-f32";
 }
 
@@ -102,8 +103,13 @@ rib_status rib_window_attn_bwd(const rib_params *p, const void *q, const void *k
     if (g.r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < valu_bwd_workspace(g))
         return RIB_ERR_WORKSPACE;
-    hipError_t e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k,
-                                   workspace, (hipStream_t)stream);
+    hipError_t e;
+    if (mfma_bwd_supported(g, p->dtype))
+        e = launch_mfma_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
+                            (hipStream_t)stream);
+    else
+        e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
+                            (hipStream_t)stream);
     return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
 }
 

@@ -61,9 +61,26 @@ hipError_t launch_valu_bwd(const Geo &g, int dtype, const void *q, const void *k
                            void *ws, hipStream_t st);
 size_t valu_bwd_workspace(const Geo &g);
 
+// Backward scratch layout (both kernel families): delta [units][N] fp32, then the
+// per-unit RIB gradient partials dF_q, dF_k [units][N][r] fp32, each 256-byte aligned.
+struct BwdWs {
+    size_t delta_off, dfq_off, dfk_off, total;
+};
+BwdWs bwd_ws_layout(const Geo &g);
+// delta[u][i] = dO[i].O[i] per head (dtype = RIB_F32 / RIB_BF16 storage of out, dout).
+hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *dout, float *delta, hipStream_t st);
+// dF[hd][e] = sum over windows (ascending) of part[(w*heads + hd)][e].
+hipError_t launch_reduce_df(const Geo &g, const float *part_q, const float *part_k, float *dfq, float *dfk,
+                            hipStream_t st);
+
 // Matrix-core forward (bf16): whether it serves this problem, and its launcher.
 bool mfma_fwd_supported(const Geo &g, int dtype);
 hipError_t launch_mfma_fwd(const Geo &g, int force_max, const void *q, const void *k, const void *v,
                            const void *fq, const void *fk, void *out, float *lse, hipStream_t st);
+// Matrix-core backward (bf16).
+bool mfma_bwd_supported(const Geo &g, int dtype);
+hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq,
+                           const void *fk, const void *out, const void *dout, const float *lse, void *dq,
+                           void *dk, void *dv, float *dfq, float *dfk, void *ws, hipStream_t st);
 
 }  // namespace rib

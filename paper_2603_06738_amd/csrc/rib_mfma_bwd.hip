@@ -1,0 +1,548 @@
+// RIB window attention, backward, on the gfx950 matrix cores (bf16 MFMA, fp32
+// accumulation).  Gradient formulas: include/rib_attn.h (chain rule through paper
+// Sec. 2.2 and Sec. 3.1 Eq. 5-6).
+//
+// Two kernels, both free of atomics so that every output is run-to-run identical:
+//
+//   dkv kernel  -- a workgroup owns 256 keys of one (window, head) unit (64 per
+//     wave, held in registers as MFMA B operands) and streams the unit's queries
+//     through LDS in tiles of 64.  Per 32x32 block it forms S = Q_aug K_aug^T and
+//     dP = dO V^T in the layout where a lane owns a KEY column, so P and dS, packed
+//     to bf16, are directly the B operands of dV^T += dO^T P and
+//     dK_aug^T += Q_aug^T dS (contractions over queries).
+//   dq kernel   -- a workgroup owns 256 queries and streams keys; it forms the
+//     TRANSPOSED blocks S^T, dP^T (a lane owns a QUERY column), so dS^T is the B
+//     operand of dQ_aug^T += K_aug^T dS^T (contraction over keys).
+//
+//   P is recomputed as exp2(S - LSE) and dS = P (dP - delta).  Neither
+//   subtraction costs a vector instruction: -LSE*log2(e), split into a bf16 high
+//   and low part, rides in the last two padding columns of Q_aug against ones in
+//   K_aug, and -delta rides the same way in the padding of dO against ones in V,
+//   so the matrix cores deliver S - LSE and dP - delta directly.
+//
+//   The last r columns of dQ_aug / dK_aug are this unit's contribution to dF_q /
+//   dF_k (Sec. 3.1: the RIB features are shared by all windows); they go to a
+//   per-unit fp32 scratch and are summed over windows in a fixed order afterwards.
+#include <mutex>
+
+#include "rib_common.h"
+
+namespace rib {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kT = 64;                 // tokens per staged tile
+constexpr int kTS = kT + 8;            // bf16 per row of a transposed tile
+constexpr int kWaves = 4;
+constexpr int kNT = kWaves * 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b)
+{
+    bf16x2 v;
+    v[0] = (__bf16)a;
+    v[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+// x as a bf16 pair (hi, lo) with hi + lo == x to ~2^-17 relative
+__device__ __forceinline__ uint32_t split_bf16(float x)
+{
+    bf16x2 v;
+    v[0] = (__bf16)x;
+    v[1] = (__bf16)(x - (float)v[0]);
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+// Column of token kappa (0..63) in a transposed tile: inside each group of 16 the
+// order in which the 32x32 accumulator layout hands its rows to the next MFMA.
+__device__ __forceinline__ int perm_col(int kappa)
+{
+    return (kappa & ~15) | (((kappa >> 2) & 1) << 3) | (((kappa >> 3) & 1) << 2) | (kappa & 3);
+}
+
+// LDS image of one 64-token tile.  X: augmented rows [64][DQK] (content | RIB | zero
+// pad | 2 extra columns) plus their transpose [64 rows][64 tokens]; Y: value-like rows
+// [64][DVK] (content | zero pad | 2 extra columns) plus the transpose of the first
+// 32 columns.  Row strides are padded for conflict-free 16-byte reads.
+template <int DQK, int DVK>
+struct Lay {
+    static constexpr int XS = DQK + 8, YS = DVK + 8;
+    static constexpr int XR = 0;
+    static constexpr int XT = XR + kT * XS;
+    static constexpr int YR = XT + 64 * kTS;
+    static constexpr int YT = YR + kT * YS;
+    static constexpr int STAGE = YT + 32 * kTS;       // bf16 elements per stage
+    static constexpr int KS = DQK / 16, VS = DVK / 16;
+    static constexpr int FP = (kT * (DQK / 2) + kNT - 1) / kNT;
+};
+
+template <int DQK, int DVK>
+struct Regs {
+    uint32_t xc[4], yc[4], xf[Lay<DQK, DVK>::FP];
+    float e0, e1;
+};
+
+// QDO = true : X = Q (scaled by sc | sp), Y = dO, extras = -LSE*log2e and -delta (hi, lo)
+// QDO = false: X = K, Y = V, extras = ones
+template <int DQK, int DVK, bool QDO>
+__device__ __forceinline__ void load_tile(Regs<DQK, DVK> &rg, const Geo &g, int hd, int64_t u, int tile,
+                                          const int *tok, const bf16_t *__restrict__ x, int64_t xstride,
+                                          const bf16_t *__restrict__ y, int64_t ystride,
+                                          const bf16_t *__restrict__ f, const float *__restrict__ lse,
+                                          const float *__restrict__ delta)
+{
+    using L = Lay<DQK, DVK>;
+    const int tid = threadIdx.x, pair = tid & 15;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        int nl = p * 16 + (tid >> 4);
+        int t = tok[tile * kT + nl];
+        uint32_t a = 0, b = 0;
+        if (t >= 0 && 2 * pair < g.d) {
+            a = *(const uint32_t *)(x + (int64_t)t * xstride + hd * g.d + 2 * pair);
+            b = *(const uint32_t *)(y + (int64_t)t * ystride + hd * g.d + 2 * pair);
+        }
+        rg.xc[p] = a;
+        rg.yc[p] = b;
+    }
+    const int n0 = tile * kT;
+    const int live = (g.N - n0 < kT ? g.N - n0 : kT) * (g.r >> 1);
+    const uint32_t *fsrc = (const uint32_t *)(f + ((int64_t)hd * g.N + n0) * g.r);
+#pragma unroll
+    for (int p = 0; p < L::FP; ++p) {
+        int e = p * kNT + tid;
+        rg.xf[p] = (e < live) ? fsrc[e] : 0u;
+    }
+    rg.e0 = 0.f;
+    rg.e1 = 0.f;
+    if (QDO && tid < kT && n0 + tid < g.N) {
+        rg.e0 = lse[u * g.N + n0 + tid];
+        rg.e1 = delta[u * g.N + n0 + tid];
+    }
+}
+
+template <int DQK, int DVK, bool QDO, bool TRANS_Y>
+__device__ __forceinline__ void store_tile(const Regs<DQK, DVK> &rg, const Geo &g, int tile, bf16_t *S, float sc,
+                                           float sp, const int *foff, const int *ftoff)
+{
+    using L = Lay<DQK, DVK>;
+    const int tid = threadIdx.x, pair = tid & 15;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        int nl = p * 16 + (tid >> 4);
+        if (2 * pair < g.d) {
+            uint32_t a = rg.xc[p], b = rg.yc[p];
+            if (QDO) a = pack_bf16(lo_bf16(a) * sc, hi_bf16(a) * sc);
+            int col = perm_col(nl);
+            *(uint32_t *)(S + L::XR + nl * L::XS + 2 * pair) = a;
+            S[L::XT + (2 * pair) * kTS + col] = (bf16_t)(a & 0xffffu);
+            S[L::XT + (2 * pair + 1) * kTS + col] = (bf16_t)(a >> 16);
+            *(uint32_t *)(S + L::YR + nl * L::YS + 2 * pair) = b;
+            if (TRANS_Y) {
+                S[L::YT + (2 * pair) * kTS + col] = (bf16_t)(b & 0xffffu);
+                S[L::YT + (2 * pair + 1) * kTS + col] = (bf16_t)(b >> 16);
+            }
+        }
+    }
+    const int fdw = kT * (g.r >> 1);
+#pragma unroll
+    for (int p = 0; p < L::FP; ++p) {
+        int e = p * kNT + tid;
+        if (e < fdw) {
+            uint32_t a = rg.xf[p];
+            if (QDO) a = pack_bf16(lo_bf16(a) * sp, hi_bf16(a) * sp);
+            *(uint32_t *)(S + L::XR + foff[p]) = a;
+            S[L::XT + ftoff[p]] = (bf16_t)(a & 0xffffu);
+            S[L::XT + ftoff[p] + kTS] = (bf16_t)(a >> 16);
+        }
+    }
+    if (tid < kT) {
+        const bool valid = tile * kT + tid < g.N;
+        uint32_t ex = 0, ey = 0;
+        if (valid) {
+            if (QDO) {
+                ex = split_bf16(-rg.e0 * kLog2e);
+                ey = split_bf16(-rg.e1);
+            } else {
+                ex = 0x3f803f80u;
+                ey = 0x3f803f80u;
+            }
+        }
+        *(uint32_t *)(S + L::XR + tid * L::XS + DQK - 2) = ex;
+        *(uint32_t *)(S + L::YR + tid * L::YS + DVK - 2) = ey;
+    }
+}
+
+// Common prologue: XCD-aware block renumbering, token table, LDS clearing, RIB offsets.
+template <int DQK, int DVK>
+__device__ __forceinline__ void prologue(const Geo &g, int nblk, int64_t &u, int &blk, int &w, int &hd, bf16_t *stages,
+                                         int *tok, int *foff, int *ftoff)
+{
+    using L = Lay<DQK, DVK>;
+    const int G = gridDim.x, per = G >> 3, rem = G & 7, xcd = blockIdx.x & 7;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    u = logical / nblk;
+    blk = logical - (int)(u * nblk);
+    w = (int)(u / g.heads);
+    hd = (int)(u - (int64_t)w * g.heads);
+    const int tid = threadIdx.x;
+    const int ntiles = (g.N + kT - 1) / kT;
+    for (int n = tid; n < ntiles * kT; n += kNT) tok[n] = n < g.N ? (int)grid_token(g, w, n) : -1;
+    uint32_t *z = (uint32_t *)stages;
+    for (int e = tid; e < L::STAGE; e += kNT) z[e] = 0u;        // 2 stages * STAGE bf16 = STAGE dwords
+#pragma unroll
+    for (int p = 0; p < L::FP; ++p) {
+        int e = p * kNT + tid, hr = g.r >> 1;
+        int tk = hr > 0 ? e / hr : 0;
+        int c = g.d + 2 * (e - tk * hr);
+        foff[p] = tk * L::XS + c;
+        ftoff[p] = c * kTS + perm_col(tk & 63);
+    }
+}
+
+template <int N>
+__device__ __forceinline__ void read_rows(bf16x8 (&dst)[N], const bf16_t *base, int stride, int row, int hf)
+{
+#pragma unroll
+    for (int t = 0; t < N; ++t) dst[t] = *(const bf16x8 *)(base + row * stride + 16 * t + 8 * hf);
+}
+
+__device__ __forceinline__ f32x16 mfma(const bf16x8 &a, const bf16x8 &b, const f32x16 &c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Store one 32-row accumulator block of an augmented gradient: rows are augmented
+// columns c = 32*mb + 8*(i/4) + 4*hf + i%4 of this lane's token.
+__device__ __forceinline__ void store_aug(const f32x16 &acc, int mb, int hf, const Geo &g, float sc, float sp,
+                                          bf16_t *grid_dst, float *part_dst)
+{
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        int c = 32 * mb + 8 * (i >> 2) + 4 * hf + (i & 3);
+        if (c < g.d) *(uint32_t *)(grid_dst + c) = pack_bf16(acc[i] * sc, acc[i + 1] * sc);
+        else if (c < g.d + g.r) *(float2 *)(part_dst + (c - g.d)) = make_float2(acc[i] * sp, acc[i + 1] * sp);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// dQ (+ dF_q partial): queries stationary, keys streamed.
+template <int DQK, int DVK>
+__global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dq_kernel(Geo g, int nblk, const bf16_t *__restrict__ q,
+                                                             const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                                             const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk,
+                                                             const bf16_t *__restrict__ dout,
+                                                             const float *__restrict__ lse, const float *__restrict__ delta,
+                                                             bf16_t *__restrict__ dq, float *__restrict__ dfq_part)
+{
+    using L = Lay<DQK, DVK>;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
+    int *tok = (int *)(smem + 2 * L::STAGE);
+
+    int64_t u;
+    int blk, w, hd, foff[L::FP], ftoff[L::FP];
+    prologue<DQK, DVK>(g, nblk, u, blk, w, hd, smem, tok, foff, ftoff);
+    __syncthreads();
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int ntiles = (g.N + kT - 1) / kT;
+    const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
+
+    Regs<DQK, DVK> rg;
+    bf16x8 Qb[2][L::KS], Gb[2][L::VS];      // stationary B operands: Q_aug' rows, dO_aug rows
+    for (int wv = 0; wv < kWaves; ++wv) {
+        int qtile = blk * kWaves + wv;
+        if (qtile < ntiles) {
+            load_tile<DQK, DVK, true>(rg, g, hd, u, qtile, tok, q, g.tstride, dout, (int64_t)g.C, fq, lse, delta);
+            store_tile<DQK, DVK, true, false>(rg, g, qtile, stage0, sc2, sp2, foff, ftoff);
+        }
+        __syncthreads();
+        if (wv == wave) {
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                read_rows<L::KS>(Qb[qb], stage0 + L::XR, L::XS, qb * 32 + col, hf);
+                read_rows<L::VS>(Gb[qb], stage0 + L::YR, L::YS, qb * 32 + col, hf);
+            }
+        }
+        __syncthreads();
+    }
+    const int q0 = (blk * kWaves + wave) * kT;
+    if (q0 >= g.N) {        // whole wave past the end: neutral operands (its results are never stored)
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+            for (int t = 0; t < L::KS; ++t)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) Qb[qb][t][i] = (__bf16)0.f;
+#pragma unroll
+            for (int t = 0; t < L::VS; ++t)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) Gb[qb][t][i] = (__bf16)0.f;
+        }
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[qb][mb][i] = 0.f;
+
+    load_tile<DQK, DVK, false>(rg, g, hd, u, 0, tok, k, g.tstride, v, g.tstride, fk, lse, delta);
+    store_tile<DQK, DVK, false, false>(rg, g, 0, stage0, 1.f, 1.f, foff, ftoff);
+    __syncthreads();
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
+        if (tile + 1 < ntiles)
+            load_tile<DQK, DVK, false>(rg, g, hd, u, tile + 1, tok, k, g.tstride, v, g.tstride, fk, lse, delta);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            bf16x8 Ak[L::KS], Av[L::VS], At[2][2];
+            read_rows<L::KS>(Ak, cur + L::XR, L::XS, kb * 32 + col, hf);
+            read_rows<L::VS>(Av, cur + L::YR, L::YS, kb * 32 + col, hf);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    At[mb][t] = *(const bf16x8 *)(cur + L::XT + (32 * mb + col) * kTS + kb * 32 + 16 * t + 8 * hf);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                f32x16 S = {0}, D = {0};
+#pragma unroll
+                for (int t = 0; t < L::KS; ++t) S = mfma(Ak[t], Qb[qb][t], S);     // S^T - LSE (log2 units)
+#pragma unroll
+                for (int t = 0; t < L::VS; ++t) D = mfma(Av[t], Gb[qb][t], D);     // dP^T - delta
+                float ds[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) ds[i] = __builtin_amdgcn_exp2f(S[i]) * D[i];
+                bf16x8 B0, B1;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) { B0[i] = (__bf16)ds[i]; B1[i] = (__bf16)ds[8 + i]; }
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    acc[qb][mb] = mfma(At[mb][0], B0, acc[qb][mb]);
+                    acc[qb][mb] = mfma(At[mb][1], B1, acc[qb][mb]);
+                }
+            }
+        }
+        if (tile + 1 < ntiles) store_tile<DQK, DVK, false, false>(rg, g, tile + 1, nxt, 1.f, 1.f, foff, ftoff);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int n = q0 + qb * 32 + col;
+        if (n >= g.N) continue;
+        bf16_t *gd = dq + (int64_t)tok[n] * g.C + hd * g.d;
+        float *pd = dfq_part + (u * g.N + n) * g.r;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) store_aug(acc[qb][mb], mb, hf, g, g.scale_c, g.scale_p, gd, pd);
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// dK, dV (+ dF_k partial): keys stationary, queries streamed.
+template <int DQK, int DVK>
+__global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dkv_kernel(Geo g, int nblk, const bf16_t *__restrict__ q,
+                                                              const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+                                                              const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk,
+                                                              const bf16_t *__restrict__ dout,
+                                                              const float *__restrict__ lse, const float *__restrict__ delta,
+                                                              bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
+                                                              float *__restrict__ dfk_part)
+{
+    using L = Lay<DQK, DVK>;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
+    int *tok = (int *)(smem + 2 * L::STAGE);
+
+    int64_t u;
+    int blk, w, hd, foff[L::FP], ftoff[L::FP];
+    prologue<DQK, DVK>(g, nblk, u, blk, w, hd, smem, tok, foff, ftoff);
+    __syncthreads();
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int ntiles = (g.N + kT - 1) / kT;
+    const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
+
+    Regs<DQK, DVK> rg;
+    bf16x8 Kb[2][L::KS], Vb[2][L::VS];      // stationary B operands: K_aug rows, V_aug rows
+    for (int wv = 0; wv < kWaves; ++wv) {
+        int ktile = blk * kWaves + wv;
+        if (ktile < ntiles) {
+            load_tile<DQK, DVK, false>(rg, g, hd, u, ktile, tok, k, g.tstride, v, g.tstride, fk, lse, delta);
+            store_tile<DQK, DVK, false, false>(rg, g, ktile, stage0, 1.f, 1.f, foff, ftoff);
+        }
+        __syncthreads();
+        if (wv == wave) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                read_rows<L::KS>(Kb[kb], stage0 + L::XR, L::XS, kb * 32 + col, hf);
+                read_rows<L::VS>(Vb[kb], stage0 + L::YR, L::YS, kb * 32 + col, hf);
+            }
+        }
+        __syncthreads();
+    }
+    const int k0 = (blk * kWaves + wave) * kT;
+    if (k0 >= g.N) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int t = 0; t < L::KS; ++t)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) Kb[kb][t][i] = (__bf16)0.f;
+#pragma unroll
+            for (int t = 0; t < L::VS; ++t)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) Vb[kb][t][i] = (__bf16)0.f;
+        }
+    }
+
+    f32x16 accV[2], accK[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) accV[kb][i] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) accK[kb][mb][i] = 0.f;
+    }
+
+    load_tile<DQK, DVK, true>(rg, g, hd, u, 0, tok, q, g.tstride, dout, (int64_t)g.C, fq, lse, delta);
+    store_tile<DQK, DVK, true, true>(rg, g, 0, stage0, sc2, sp2, foff, ftoff);
+    __syncthreads();
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
+        if (tile + 1 < ntiles)
+            load_tile<DQK, DVK, true>(rg, g, hd, u, tile + 1, tok, q, g.tstride, dout, (int64_t)g.C, fq, lse, delta);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            bf16x8 Aq[L::KS], Ag[L::VS], Aqt[2][2], Agt[2];
+            read_rows<L::KS>(Aq, cur + L::XR, L::XS, qb * 32 + col, hf);
+            read_rows<L::VS>(Ag, cur + L::YR, L::YS, qb * 32 + col, hf);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                Agt[t] = *(const bf16x8 *)(cur + L::YT + col * kTS + qb * 32 + 16 * t + 8 * hf);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    Aqt[mb][t] = *(const bf16x8 *)(cur + L::XT + (32 * mb + col) * kTS + qb * 32 + 16 * t + 8 * hf);
+            }
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                f32x16 S = {0}, D = {0};
+#pragma unroll
+                for (int t = 0; t < L::KS; ++t) S = mfma(Aq[t], Kb[kb][t], S);     // S - LSE (log2 units)
+#pragma unroll
+                for (int t = 0; t < L::VS; ++t) D = mfma(Ag[t], Vb[kb][t], D);     // dP - delta
+                float p[16], ds[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    p[i] = __builtin_amdgcn_exp2f(S[i]);
+                    ds[i] = p[i] * D[i];
+                }
+                bf16x8 P0, P1, B0, B1;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    P0[i] = (__bf16)p[i];
+                    P1[i] = (__bf16)p[8 + i];
+                    B0[i] = (__bf16)ds[i];
+                    B1[i] = (__bf16)ds[8 + i];
+                }
+                accV[kb] = mfma(Agt[0], P0, accV[kb]);
+                accV[kb] = mfma(Agt[1], P1, accV[kb]);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    accK[kb][mb] = mfma(Aqt[mb][0], B0, accK[kb][mb]);
+                    accK[kb][mb] = mfma(Aqt[mb][1], B1, accK[kb][mb]);
+                }
+            }
+        }
+        if (tile + 1 < ntiles) store_tile<DQK, DVK, true, true>(rg, g, tile + 1, nxt, sc2, sp2, foff, ftoff);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        const int n = k0 + kb * 32 + col;
+        if (n >= g.N) continue;
+        const int64_t base = (int64_t)tok[n] * g.C + hd * g.d;
+        float *pd = dfk_part + (u * g.N + n) * g.r;
+        // Q_aug' carries log2(e): undo it here
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) store_aug(accK[kb][mb], mb, hf, g, kLn2, kLn2, dk + base, pd);
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            int c = 8 * (i >> 2) + 4 * hf + (i & 3);
+            if (c < g.d) *(uint32_t *)(dv + base + c) = pack_bf16(accV[kb][i], accV[kb][i + 1]);
+        }
+    }
+}
+
+template <int DQK, int DVK>
+hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
+                  const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv, float *dfq,
+                  float *dfk, void *ws, hipStream_t st)
+{
+    using L = Lay<DQK, DVK>;
+    const BwdWs l = bwd_ws_layout(g);
+    float *delta = (float *)((char *)ws + l.delta_off);
+    float *pq = (float *)((char *)ws + l.dfq_off);
+    float *pk = (float *)((char *)ws + l.dfk_off);
+    hipError_t e = launch_delta(g, RIB_BF16, out, dout, delta, st);
+    if (e != hipSuccess) return e;
+
+    const int ntiles = (g.N + kT - 1) / kT;
+    const int nblk = (ntiles + kWaves - 1) / kWaves;
+    const size_t smem = (size_t)2 * L::STAGE * sizeof(bf16_t) + (size_t)ntiles * kT * sizeof(int);
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dq_kernel<DQK, DVK>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    const dim3 grid((unsigned)(g.units * nblk)), block(kNT);
+    hipLaunchKernelGGL((mfma_bwd_dkv_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
+                       (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,
+                       (const bf16_t *)dout, lse, delta, (bf16_t *)dk, (bf16_t *)dv, pk);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((mfma_bwd_dq_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
+                       (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,
+                       (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return launch_reduce_df(g, pq, pk, dfq, dfk, st);
+}
+
+}  // namespace
+
+bool mfma_bwd_supported(const Geo &g, int dtype)
+{
+    return dtype == RIB_BF16 && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 && g.d + g.r + 2 <= 64 && g.N >= 64 &&
+           g.N <= 9216 && (g.tstride & 1) == 0;
+}
+
+hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
+                           const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv,
+                           float *dfq, float *dfk, void *ws, hipStream_t st)
+{
+    const bool small_qk = g.d + g.r + 2 <= 48, small_v = g.d + 2 <= 32;
+    if (small_qk && small_v) return launch<48, 32>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
+    if (small_v) return launch<64, 32>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
+    return launch<64, 48>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
+}
+
+}  // namespace rib

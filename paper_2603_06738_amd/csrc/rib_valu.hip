@@ -327,20 +327,7 @@ __global__ __launch_bounds__(kThreads) void reduce_df_kernel(Geo g, const float 
 }
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-struct BwdWs {
-    size_t delta_off, dfq_off, dfk_off, total;
-};
-inline BwdWs ws_layout(const Geo &g)
-{
-    BwdWs l;
-    size_t rows = (size_t)g.units * g.N;
-    l.delta_off = 0;
-    l.dfq_off = align256(rows * sizeof(float));
-    l.dfk_off = l.dfq_off + align256(rows * g.r * sizeof(float));
-    l.total = l.dfk_off + align256(rows * g.r * sizeof(float));
-    return l;
-}
+inline BwdWs ws_layout(const Geo &g) { return bwd_ws_layout(g); }
 
 template <typename T, int DA, int DV>
 hipError_t fwd_t(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
@@ -363,9 +350,8 @@ hipError_t bwd_t(const Geo &g, const void *q, const void *k, const void *v, cons
     float *pq = (float *)((char *)ws + l.dfq_off);
     float *pk = (float *)((char *)ws + l.dfk_off);
     int64_t rows = g.units * g.N;
-    hipLaunchKernelGGL((valu_delta_kernel<T>), dim3((unsigned)((rows + kThreads - 1) / kThreads)), dim3(kThreads), 0,
-                       st, g, (const T *)out, (const T *)dout, delta);
-    hipError_t e = hipGetLastError();
+    (void)rows;
+    hipError_t e = launch_delta(g, sizeof(T) == 2 ? RIB_BF16 : RIB_F32, out, dout, delta, st);
     if (e != hipSuccess) return e;
     int nblk = (g.N + kRows - 1) / kRows;
     dim3 grid((unsigned)(g.units * nblk));
@@ -379,13 +365,7 @@ hipError_t bwd_t(const Geo &g, const void *q, const void *k, const void *v, cons
                        (T *)dv, pk);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (g.r > 0) {
-        int64_t n = (int64_t)g.heads * g.N * g.r;
-        hipLaunchKernelGGL(reduce_df_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads), 2), dim3(kThreads), 0, st,
-                           g, pq, pk, dfq, dfk);
-        e = hipGetLastError();
-    }
-    return e;
+    return launch_reduce_df(g, pq, pk, dfq, dfk, st);
 }
 
 // Smallest compiled (DA, DV) bucket holding d + r and d.
@@ -401,6 +381,40 @@ inline int bucket(const Geo &g)
 }  // namespace
 
 size_t valu_bwd_workspace(const Geo &g) { return ws_layout(g).total; }
+
+BwdWs bwd_ws_layout(const Geo &g)
+{
+    BwdWs l;
+    size_t rows = (size_t)g.units * g.N;
+    l.delta_off = 0;
+    l.dfq_off = align256(rows * sizeof(float));
+    l.dfk_off = l.dfq_off + align256(rows * g.r * sizeof(float));
+    l.total = l.dfk_off + align256(rows * g.r * sizeof(float));
+    return l;
+}
+
+hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *dout, float *delta, hipStream_t st)
+{
+    const int64_t rows = g.units * g.N;
+    dim3 grid((unsigned)((rows + kThreads - 1) / kThreads));
+    if (dtype == RIB_BF16)
+        hipLaunchKernelGGL((valu_delta_kernel<bf16_t>), grid, dim3(kThreads), 0, st, g, (const bf16_t *)out,
+                           (const bf16_t *)dout, delta);
+    else
+        hipLaunchKernelGGL((valu_delta_kernel<float>), grid, dim3(kThreads), 0, st, g, (const float *)out,
+                           (const float *)dout, delta);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_df(const Geo &g, const float *part_q, const float *part_k, float *dfq, float *dfk,
+                            hipStream_t st)
+{
+    if (g.r == 0) return hipSuccess;
+    const int64_t n = (int64_t)g.heads * g.N * g.r;
+    hipLaunchKernelGGL(reduce_df_kernel, dim3((unsigned)((n + kThreads - 1) / kThreads), 2), dim3(kThreads), 0, st, g,
+                       part_q, part_k, dfq, dfk);
+    return hipGetLastError();
+}
 
 #define RIB_VALU_DISPATCH(FN, ...)                                                         \
     switch (bucket(g) * 2 + (dtype == RIB_BF16 ? 1 : 0)) {                                 \

@@ -33,7 +33,9 @@ rib_status make_geo(const rib_params *p, Geo *g)
     g->units = (int64_t)p->B * g->nwx * g->nwy * p->heads;
     // every kernel indexes workgroups with 32-bit block ids and tokens with int
     const int64_t blocks = g->units * ((g->N + 63) / 64);
-    if (blocks > 0x7fffffffLL || (int64_t)p->B * p->H * p->W > 0x7fffffffLL) return RIB_ERR_UNSUPPORTED;
+    if (blocks > 0x7fffffffLL || (int64_t)p->B * p->H * p->W > 0x7fffffffLL ||
+        g->units * g->N > ((int64_t)1 << 34))
+        return RIB_ERR_UNSUPPORTED;
     return RIB_OK;
 }
 

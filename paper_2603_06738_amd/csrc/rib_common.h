@@ -22,6 +22,10 @@ struct Geo {
 
 using bf16_t = uint16_t;  // raw bf16 storage
 
+// Dynamic LDS the matrix-core kernels may ask for: the 160 KB of a gfx950 CU minus room
+// for the few hundred bytes of static LDS the compiler adds (workgroup reductions).
+constexpr int kMaxDynLds = 160 * 1024 - 2048;
+
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
 

@@ -507,10 +507,10 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
         attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dq_kernel<DQK, DVK>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
         if (attr_err == hipSuccess)
             attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
     });
     if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(g.units * nblk)), block(kNT);

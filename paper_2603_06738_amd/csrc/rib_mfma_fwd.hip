@@ -28,6 +28,8 @@
 //   maximum that is raised lazily (only when a tile exceeds it by 2^8) and is
 //   subtracted for free as the C operand of the score MFMA.  Both paths compute
 //   the exact softmax up to rounding.
+#include <mutex>
+
 #include "rib_common.h"
 
 namespace rib {
@@ -253,8 +255,265 @@ __device__ __forceinline__ void attend(const Geo &g, int hd, const int *tok, bf1
     }
 }
 
-template <int DQK, int WAVES, bool ONES>
-__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void mfma_fwd_kernel(
+
+// ---------------------------------------------------------------------------------------
+// Fast path: full tiles of 128 keys, no masking, no running maximum, and a hand-ordered
+// software pipeline.  For the 32x32 block s of a tile the wave issues, interleaved,
+//   the 3 score MFMAs of block s+1, the 16 exp2 + 8 bf16 packs of block s, and the
+//   2 PV MFMAs of block s-1,
+// so the matrix pipe and the vector ALU work on independent data all the time; the
+// staging of the next tile (global loads early, LDS writes late) rides in the gaps.
+// Scheduling fences keep the compiler from regrouping the instruction stream.
+constexpr int kFT = 128;            // keys per tile
+constexpr int kFVS = kFT + 8;       // bf16 per V^T row (272 B: conflict-free 16-byte reads)
+// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
+#define RIB_SG_VALU 0x002
+#define RIB_SG_MFMA 0x008
+#define RIB_SG_VMEM_RD 0x020
+#define RIB_SG_DS_RD 0x100
+#define RIB_SG_DS_WR 0x200
+#define RIB_SG_TRANS 0x400
+#define RIB_SG(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+
+template <int DQK>
+struct FastRegs {
+    uint32_t kx[8], vx[8], fa[8];
+    uint32_t fb[DQK == 64 ? 8 : 1];     // second RIB dword per lane: rows of up to 32 dwords
+};
+
+template <int DQK>
+struct FastConst {                  // per-thread staging constants
+    uint32_t lane_c;                // byte offset of this lane's channel pair inside a token
+    uint32_t tsb;                   // token stride in bytes
+    int tok_idx;                    // first of this lane's 8 tokens inside a tile
+    uint32_t f_off0, f_off1;        // byte offsets of this lane's RIB dwords inside a RIB row
+    int k_dst, f_dst0, f_dst1, v_dst;   // bf16 element offsets inside a stage
+};
+
+template <int DQK>
+__device__ __forceinline__ FastConst<DQK> fast_const(const Geo &g, int hd)
+{
+    constexpr int KSTR = DQK + 8;
+    FastConst<DQK> c;
+    const int tid = threadIdx.x, grp = tid >> 4, j = tid & 15;
+    const int hp = g.d >> 1, rh = g.r >> 1;
+    const int pair = j < hp ? j : hp - 1;               // idle lanes duplicate a neighbour's work
+    const int f0 = j < rh ? j : rh - 1;                 // (the fast path requires r > 0)
+    const int f1 = 16 + j < rh ? 16 + j : rh - 1;
+    c.lane_c = (uint32_t)(hd * g.d + 2 * pair) * 2u;
+    c.tsb = (uint32_t)g.tstride * 2u;
+    c.tok_idx = grp * 8;
+    c.f_off0 = (uint32_t)f0 * 4u;
+    c.f_off1 = (uint32_t)f1 * 4u;
+    c.k_dst = grp * 8 * KSTR + 2 * pair;
+    c.f_dst0 = grp * 8 * KSTR + g.d + 2 * f0;
+    c.f_dst1 = grp * 8 * KSTR + g.d + 2 * f1;
+    c.v_dst = (2 * pair) * kFVS + 16 * (grp >> 1) + 4 * (grp & 1);
+    return c;
+}
+
+// global loads of token p (0..7) of this lane's group for tile `tile`
+template <int DQK>
+__device__ __forceinline__ void fast_load(FastRegs<DQK> &rg, const FastConst<DQK> &c, const Geo &g, int p, const int *tokt,
+                                          const char *kb, const char *vb, const char *fb)
+{
+    const uint32_t off = __umul24((uint32_t)tokt[c.tok_idx + p], c.tsb) + c.lane_c;
+    rg.kx[p] = *(const uint32_t *)(kb + off);
+    rg.vx[p] = *(const uint32_t *)(vb + off);
+    const uint32_t row = (uint32_t)(c.tok_idx + p) * (uint32_t)(g.r * 2);
+    rg.fa[p] = *(const uint32_t *)(fb + row + c.f_off0);
+    if (DQK == 64) rg.fb[p] = *(const uint32_t *)(fb + row + c.f_off1);
+}
+
+// LDS writes of token p: K_aug row pieces; V^T after every 4th token (4 keys per 8-byte write)
+template <int DQK>
+__device__ __forceinline__ void fast_store(const FastRegs<DQK> &rg, const FastConst<DQK> &c, int p, bf16_t *Kf, bf16_t *Vf)
+{
+    constexpr int KSTR = DQK + 8;
+    *(uint32_t *)(Kf + c.k_dst + p * KSTR) = rg.kx[p];
+    *(uint32_t *)(Kf + c.f_dst0 + p * KSTR) = rg.fa[p];
+    if (DQK == 64) *(uint32_t *)(Kf + c.f_dst1 + p * KSTR) = rg.fb[p];
+    if ((p & 3) == 3) {
+        const int h = p >> 2;
+        const uint32_t a = rg.vx[p - 3], b = rg.vx[p - 2], cc = rg.vx[p - 1], d = rg.vx[p];
+        uint2 even, odd;
+        even.x = __builtin_amdgcn_perm(b, a, 0x05040100u);
+        even.y = __builtin_amdgcn_perm(d, cc, 0x05040100u);
+        odd.x = __builtin_amdgcn_perm(b, a, 0x07060302u);
+        odd.y = __builtin_amdgcn_perm(d, cc, 0x07060302u);
+        *(uint2 *)(Vf + c.v_dst + 8 * h) = even;
+        *(uint2 *)(Vf + c.v_dst + kFVS + 8 * h) = odd;
+    }
+}
+
+template <int DQK, bool ONES>
+__device__ __forceinline__ void attend_fast(const Geo &g, int hd, const int *tok, bf16_t *Kf, bf16_t *Vf,
+                                            const bf16x8 (&Q)[2][DQK / 16], const bf16_t *__restrict__ k,
+                                            const bf16_t *__restrict__ v, const bf16_t *__restrict__ fk,
+                                            f32x16 (&O)[2], float (&lsum)[2])
+{
+    constexpr int KS = DQK / 16, KSTR = DQK + 8;
+    constexpr int KSZ = kFT * KSTR, VSZ = 32 * kFVS;     // bf16 per stage
+    const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
+    const int ntiles = g.N / kFT;
+    const FastConst<DQK> c = fast_const<DQK>(g, hd);
+    const char *kbase = (const char *)k, *vbase = (const char *)v;
+    const char *fbase = (const char *)(fk + (int64_t)hd * g.N * g.r);
+    const uint32_t ftile = (uint32_t)kFT * (uint32_t)(g.r * 2);
+
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[qb][i] = 0.f;
+        lsum[qb] = 0.f;
+    }
+
+    FastRegs<DQK> rg;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) fast_load<DQK>(rg, c, g, p, tok, kbase, vbase, fbase);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) fast_store<DQK>(rg, c, p, Kf, Vf);
+    __syncthreads();
+
+    const f32x16 zero = {0};
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int cur = tile & 1;
+        const bf16_t *Kc = Kf + cur * KSZ, *Vc = Vf + cur * VSZ;
+        bf16_t *Kn = Kf + (cur ^ 1) * KSZ, *Vn = Vf + (cur ^ 1) * VSZ;
+        const int nt = tile + 1 < ntiles ? tile + 1 : tile;       // the last tile re-stages itself (unused)
+        const int *tokn = tok + nt * kFT;
+        const char *fn = fbase + (uint32_t)nt * ftile;
+
+        bf16x8 Ak[4][KS], Av[4][2];
+        f32x16 S[2];
+        bf16x8 P[2][2];
+#pragma unroll
+        for (int t = 0; t < KS; ++t) Ak[0][t] = *(const bf16x8 *)(Kc + col * KSTR + 16 * t + 8 * hf);
+#pragma unroll
+        for (int t = 0; t < 2; ++t) Av[0][t] = *(const bf16x8 *)(Vc + col * kFVS + 16 * t + 8 * hf);
+        S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[0][0], Q[0][0], zero, 0, 0, 0);
+#pragma unroll
+        for (int t = 1; t < KS; ++t) S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[0][t], Q[0][t], S[0], 0, 0, 0);
+
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int kb = s >> 1, qb = s & 1, cs = s & 1, ns = cs ^ 1;
+            const int s1 = s + 1, kb1 = s1 >> 1, qb1 = s1 & 1;
+            const int kbp = (s - 1) >> 1, qbp = (s - 1) & 1;
+            float pe[16];
+            // group 0..2: one score MFMA of the next block + 4 exp2 and 2 packs of this block
+#pragma unroll
+            for (int grp = 0; grp < 4; ++grp) {
+                if (grp < 3) {
+                    if (s < 7 && grp < 2) {
+                        S[ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[kb1][grp], Q[qb1][grp],
+                                                                         grp == 0 ? zero : S[ns], 0, 0, 0);
+                    }
+                    if (s < 7 && grp == 2) {
+#pragma unroll
+                        for (int t = 2; t < KS; ++t)
+                            S[ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[kb1][t], Q[qb1][t], S[ns], 0, 0, 0);
+                    }
+                } else if (s > 0) {
+                    O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][0], P[ns][0], O[qbp], 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 4 * grp; i < 4 * grp + 4; ++i) pe[i] = __builtin_amdgcn_exp2f(S[cs][i]);
+                if (!ONES) lsum[qb] += (pe[4 * grp] + pe[4 * grp + 1]) + (pe[4 * grp + 2] + pe[4 * grp + 3]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) P[cs][grp >> 1][4 * (grp & 1) + i] = (__bf16)pe[4 * grp + i];
+            }
+            // group 4: second PV MFMA of the previous block + this step's share of the staging
+            if (s > 0) O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][1], P[ns][1], O[qbp], 0, 0, 0);
+            if (qb == 0 && kb + 1 < 4) {
+#pragma unroll
+                for (int t = 0; t < KS; ++t)
+                    Ak[kb + 1][t] = *(const bf16x8 *)(Kc + ((kb + 1) * 32 + col) * KSTR + 16 * t + 8 * hf);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    Av[kb + 1][t] = *(const bf16x8 *)(Vc + col * kFVS + (kb + 1) * 32 + 16 * t + 8 * hf);
+            }
+            if (s < 4) {
+                fast_load<DQK>(rg, c, g, 2 * s, tokn, kbase, vbase, fn);
+                fast_load<DQK>(rg, c, g, 2 * s + 1, tokn, kbase, vbase, fn);
+            } else {
+                fast_store<DQK>(rg, c, 2 * (s - 4), Kn, Vn);
+                fast_store<DQK>(rg, c, 2 * (s - 4) + 1, Kn, Vn);
+            }
+        }
+        // drain: PV of the last block
+        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][0], P[1][0], O[1], 0, 0, 0);
+        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][1], P[1][1], O[1], 0, 0, 0);
+
+        // The order the scheduler is asked to build out of the block above: first the KS
+        // MFMAs of block 0; then, per block, each MFMA followed by its share of exp2 / pack
+        // work, with the operand reads and the staging traffic behind the fifth MFMA.
+        RIB_SG(RIB_SG_DS_RD, KS + 2);
+        RIB_SG(RIB_SG_MFMA, KS);
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const int nm = (s < 7 ? KS : 0) + (s > 0 ? 2 : 0);      // MFMAs issued in this step
+#pragma unroll
+            for (int m = 0; m < 5; ++m) {
+                if (m < nm) RIB_SG(RIB_SG_MFMA, 1);
+                if (m < 4) {
+                    RIB_SG(RIB_SG_TRANS, 4);
+                    RIB_SG(RIB_SG_VALU, ONES ? 2 : 5);
+                } else {
+                    if (nm > 5) RIB_SG(RIB_SG_MFMA, 1);
+                    if ((s & 1) == 0 && s < 6) RIB_SG(RIB_SG_DS_RD, KS + 2);
+                    if (s < 4) {
+                        RIB_SG(RIB_SG_DS_RD, 2);
+                        RIB_SG(RIB_SG_VALU, 4);
+                        RIB_SG(RIB_SG_VMEM_RD, DQK == 64 ? 8 : 6);
+                    } else {
+                        RIB_SG(RIB_SG_VALU, 4);
+                        RIB_SG(RIB_SG_DS_WR, DQK == 64 ? 8 : 6);
+                    }
+                }
+            }
+        }
+        RIB_SG(RIB_SG_MFMA, 2);
+        __syncthreads();
+    }
+}
+
+// Constant parts of the generic (64-key) LDS tiles: zero padding columns of K_aug, the
+// ones row and the zero rows of V^T.  The staging code never writes them.
+template <int DQK, int NT, bool ONES>
+__device__ __forceinline__ void init_generic_tiles(const Geo &g, bf16_t *Ka, bf16_t *Vt)
+{
+    constexpr int KSTR = DQK + 8;
+    for (int e = threadIdx.x; e < 2 * kTK * KSTR; e += NT)
+        if (e % KSTR >= g.d + g.r) Ka[e] = 0;
+    for (int e = threadIdx.x; e < 2 * 32 * kVStr; e += NT) {
+        int row = (e % (32 * kVStr)) / kVStr;
+        if (row >= g.d) Vt[e] = (ONES && row == g.d) ? (bf16_t)0x3f80 : (bf16_t)0;
+    }
+}
+template <int DQK, int NT, bool ONES>
+__device__ __forceinline__ void init_fast_tiles(const Geo &g, bf16_t *Kf, bf16_t *Vf)
+{
+    constexpr int KSTR = DQK + 8;
+    for (int e = threadIdx.x; e < 2 * kFT * KSTR; e += NT)
+        if (e % KSTR >= g.d + g.r) Kf[e] = 0;
+    for (int e = threadIdx.x; e < 2 * 32 * kFVS; e += NT) {
+        int row = (e % (32 * kFVS)) / kFVS;
+        if (row >= g.d) Vf[e] = (ONES && row == g.d) ? (bf16_t)0x3f80 : (bf16_t)0;
+    }
+}
+
+template <int DQK, bool FAST>
+struct FwdSmem {
+    static constexpr int KSTR = DQK + 8;
+    static constexpr int GEN_K = 2 * kTK * KSTR, GEN_V = 2 * 32 * kVStr;       // bf16 elements
+    static constexpr int FAST_K = 2 * kFT * KSTR, FAST_V = 2 * 32 * kFVS;
+    static constexpr int TILE_ELEMS = FAST ? (FAST_K + FAST_V) : (GEN_K + GEN_V);
+    static constexpr size_t TILE_BYTES = (size_t)TILE_ELEMS * sizeof(bf16_t);
+};
+
+template <int DQK, int WAVES, bool ONES, bool FAST>
+__global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
     Geo g, int nqblk, int force_max, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
     const bf16_t *__restrict__ v, const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk,
     bf16_t *__restrict__ out, float *__restrict__ lse)
@@ -263,9 +522,13 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void mfma_fwd_kerne
     constexpr int KS = DQK / 16;
     constexpr int KSTR = DQK + 8;
     using St = Stage<DQK, WAVES>;
-    __shared__ __attribute__((aligned(16))) bf16_t Ka[2][kTK * KSTR];
-    __shared__ __attribute__((aligned(16))) bf16_t Vt[2][32 * kVStr];
-    extern __shared__ int tok[];   // [ntiles*64] grid token of each window-local token, -1 past N
+    using Sm = FwdSmem<DQK, FAST>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *tiles = (bf16_t *)smem;
+    bf16_t(*Ka)[kTK * KSTR] = (bf16_t(*)[kTK * KSTR]) tiles;                   // generic layout
+    bf16_t(*Vt)[32 * kVStr] = (bf16_t(*)[32 * kVStr])(tiles + Sm::GEN_K);
+    bf16_t *Kf = tiles, *Vf = tiles + Sm::FAST_K;                               // fast layout (same memory)
+    int *tok = (int *)(smem + Sm::TILE_BYTES);   // [ntiles*64] grid token of each window-local token, -1 past N
 
     // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that each XCD
     // works on a contiguous range of (unit, query block) and its L2 sees all users
@@ -280,16 +543,7 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void mfma_fwd_kerne
     const int ntiles = (g.N + kTK - 1) / kTK;
 
     for (int n = tid; n < ntiles * kTK; n += NT) tok[n] = n < g.N ? (int)grid_token(g, w, n) : -1;
-    // constant parts of the LDS tiles: zero padding columns of K_aug, the ones row and
-    // zero rows of V^T (the staging code never writes them)
-    for (int e = tid; e < 2 * kTK * KSTR; e += NT) {
-        int c = e % KSTR;
-        if (c >= g.d + g.r) Ka[0][e] = 0;
-    }
-    for (int e = tid; e < 2 * 32 * kVStr; e += NT) {
-        int row = (e % (32 * kVStr)) / kVStr;
-        if (row >= g.d) Vt[0][e] = (ONES && row == g.d) ? (bf16_t)0x3f80 : (bf16_t)0;
-    }
+    init_generic_tiles<DQK, NT, ONES>(g, Ka[0], Vt[0]);
     int foff[St::FP];
 #pragma unroll
     for (int p = 0; p < St::FP; ++p) {
@@ -332,10 +586,16 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void mfma_fwd_kerne
     }
 
     f32x16 O[2];
-    float mrun[2], lsum[2];
+    float mrun[2] = {0.f, 0.f}, lsum[2];
     bool redo = force_max != 0;
     if (!redo) {
-        attend<DQK, WAVES, ONES, false>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
+        if (FAST) {
+            init_fast_tiles<DQK, NT, ONES>(g, Kf, Vf);
+            __syncthreads();
+            attend_fast<DQK, ONES>(g, hd, tok, Kf, Vf, Q, k, v, fk, O, lsum);
+        } else {
+            attend<DQK, WAVES, ONES, false>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
+        }
         bool bad = false;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -344,6 +604,10 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void mfma_fwd_kerne
             if (!ok && q0 + qb * 32 + col < g.N) bad = true;
         }
         redo = __syncthreads_or(bad);
+        if (FAST && redo) {
+            init_generic_tiles<DQK, NT, ONES>(g, Ka[0], Vt[0]);
+            __syncthreads();
+        }
     }
     if (redo) attend<DQK, WAVES, ONES, true>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
 
@@ -369,18 +633,33 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void mfma_fwd_kerne
     }
 }
 
-template <int DQK, bool ONES>
+template <int DQK, bool ONES, bool FAST>
 hipError_t launch(const Geo &g, int force_max, const void *q, const void *k, const void *v, const void *fq,
                   const void *fk, void *out, float *lse, hipStream_t st)
 {
     constexpr int WAVES = 4;
     const int nqblk = (g.N + WAVES * 64 - 1) / (WAVES * 64);
     const int ntiles = (g.N + kTK - 1) / kTK;
-    const size_t dyn = (size_t)ntiles * kTK * sizeof(int);
-    hipLaunchKernelGGL((mfma_fwd_kernel<DQK, WAVES, ONES>), dim3((unsigned)(g.units * nqblk)), dim3(WAVES * 64), dyn,
-                       st, g, nqblk, force_max, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                       (const bf16_t *)fq, (const bf16_t *)fk, (bf16_t *)out, lse);
+    const size_t dyn = FwdSmem<DQK, FAST>::TILE_BYTES + (size_t)ntiles * kTK * sizeof(int);
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [] {
+        attr_err = hipFuncSetAttribute((const void *)mfma_fwd_kernel<DQK, WAVES, ONES, FAST>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    hipLaunchKernelGGL((mfma_fwd_kernel<DQK, WAVES, ONES, FAST>), dim3((unsigned)(g.units * nqblk)),
+                       dim3(WAVES * 64), dyn, st, g, nqblk, force_max, (const bf16_t *)q, (const bf16_t *)k,
+                       (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk, (bf16_t *)out, lse);
     return hipGetLastError();
+}
+
+template <int DQK, bool ONES>
+hipError_t launch_pick(const Geo &g, bool fast, int force_max, const void *q, const void *k, const void *v,
+                       const void *fq, const void *fk, void *out, float *lse, hipStream_t st)
+{
+    return fast ? launch<DQK, ONES, true>(g, force_max, q, k, v, fq, fk, out, lse, st)
+                : launch<DQK, ONES, false>(g, force_max, q, k, v, fq, fk, out, lse, st);
 }
 
 }  // namespace
@@ -391,15 +670,25 @@ bool mfma_fwd_supported(const Geo &g, int dtype)
            g.N <= 9216 && (g.tstride & 1) == 0;
 }
 
+// The pipelined fast path needs whole 128-key tiles and 32-bit byte offsets built with
+// a 24-bit multiply.
+static bool fast_ok(const Geo &g)
+{
+    const int64_t tokens = (int64_t)g.B * g.H * g.W;
+    const bool small_r = (g.d + g.r <= 48) ? (g.r <= 32) : true;
+    return g.r > 0 && g.N % kFT == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+           tokens * g.tstride * 2 < ((int64_t)1 << 32) && small_r;
+}
+
 hipError_t launch_mfma_fwd(const Geo &g, int force_max, const void *q, const void *k, const void *v, const void *fq,
                            const void *fk, void *out, float *lse, hipStream_t st)
 {
-    const bool ones = g.d < 32;
+    const bool ones = g.d < 32, fast = fast_ok(g);
     if (g.d + g.r <= 48)
-        return ones ? launch<48, true>(g, force_max, q, k, v, fq, fk, out, lse, st)
-                    : launch<48, false>(g, force_max, q, k, v, fq, fk, out, lse, st);
-    return ones ? launch<64, true>(g, force_max, q, k, v, fq, fk, out, lse, st)
-                : launch<64, false>(g, force_max, q, k, v, fq, fk, out, lse, st);
+        return ones ? launch_pick<48, true>(g, fast, force_max, q, k, v, fq, fk, out, lse, st)
+                    : launch_pick<48, false>(g, fast, force_max, q, k, v, fq, fk, out, lse, st);
+    return ones ? launch_pick<64, true>(g, fast, force_max, q, k, v, fq, fk, out, lse, st)
+                : launch_pick<64, false>(g, fast, force_max, q, k, v, fq, fk, out, lse, st);
 }
 
 }  // namespace rib

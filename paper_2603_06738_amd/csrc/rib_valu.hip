@@ -152,20 +152,31 @@ __global__ __launch_bounds__(kThreads) void valu_fwd_kernel(Geo g, int nblk, con
     if (lse != nullptr && part == 0) lse[u * g.N + i] = (m + log2f(l)) * kLn2;
 }
 
-// delta[u][i] = dO[i] . O[i] over the head's channels.
+// delta[u][i] = dO[i] . O[i] over the head's channels.  Sixteen lanes share one
+// (token, head): consecutive groups are the heads of one token, so a wave reads whole
+// contiguous token rows of O and dO; each lane multiplies its share of the d channels
+// and the group adds up with lane shuffles.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, const T *__restrict__ out,
                                                               const T *__restrict__ dout, float *__restrict__ delta)
 {
-    int64_t idx = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (idx >= g.units * g.N) return;
-    int64_t u = idx / g.N;
-    int n = (int)(idx - u * g.N);
-    int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
-    int64_t base = grid_token(g, w, n) * g.C + hd * g.d;
+    const int64_t grp = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 4;   // (w*N + n)*heads + hd
+    const int sub = threadIdx.x & 15;
+    const int64_t total = g.units * g.N;
     float acc = 0.f;
-    for (int t = 0; t < g.d; ++t) acc = fmaf(widen(out[base + t]), widen(dout[base + t]), acc);
-    delta[idx] = acc;
+    int hd = 0, n = 0;
+    int64_t w = 0;
+    if (grp < total) {
+        hd = (int)(grp % g.heads);
+        const int64_t wn = grp / g.heads;
+        w = wn / g.N;
+        n = (int)(wn - w * g.N);
+        const int64_t base = grid_token(g, (int)w, n) * g.C + hd * g.d;
+        for (int t = sub; t < g.d; t += 16) acc = fmaf(widen(out[base + t]), widen(dout[base + t]), acc);
+    }
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+    if (grp < total && sub == 0) delta[(w * g.heads + hd) * g.N + n] = acc;
 }
 
 // dQ and this unit's dF_q contribution: rows are queries, tiles are keys.
@@ -396,7 +407,7 @@ BwdWs bwd_ws_layout(const Geo &g)
 hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *dout, float *delta, hipStream_t st)
 {
     const int64_t rows = g.units * g.N;
-    dim3 grid((unsigned)((rows + kThreads - 1) / kThreads));
+    dim3 grid((unsigned)((rows * 16 + kThreads - 1) / kThreads));
     if (dtype == RIB_BF16)
         hipLaunchKernelGGL((valu_delta_kernel<bf16_t>), grid, dim3(kThreads), 0, st, g, (const bf16_t *)out,
                            (const bf16_t *)dout, delta);

@@ -52,6 +52,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b)
     v[1] = (__bf16)b;
     return __builtin_bit_cast(uint32_t, v);
 }
+// Two fp32 -> one dword of two bf16 by dropping the low 16 bits (round toward zero).
+__device__ __forceinline__ uint32_t trunc_pack(float lo, float hi)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &w) { return __builtin_bit_cast(bf16x8, w); }
+// Mean relative loss of truncating to bf16 (spacing 2^-7, mantissa log-uniform in [1,2)):
+// 2^-8 / (2 ln 2) * ... = 2^-8 * 0.7213; as a log2 it is added back to the softmax denominator's log.
+constexpr float kTruncLog2 = 0.0040593f;
 __device__ __forceinline__ float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -275,6 +284,19 @@ constexpr int kFVS = kFT + 8;       // bf16 per V^T row (272 B: conflict-free 16
 #define RIB_SG_TRANS 0x400
 #define RIB_SG(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 
+// Emits, for m = M0 .. M1-1: one MFMA, then 3 or 4 transcendentals (16 per 5 MFMAs),
+// then 2 vector-ALU instructions.
+template <int M0, int M1>
+__device__ __forceinline__ void sched_pipeline()
+{
+    if constexpr (M0 < M1) {
+        RIB_SG(RIB_SG_MFMA, 1);
+        RIB_SG(RIB_SG_TRANS, (M0 % 5) == 4 ? 4 : 3);
+        RIB_SG(RIB_SG_VALU, 2);
+        sched_pipeline<M0 + 1, M1>();
+    }
+}
+
 template <int DQK>
 struct FastRegs {
     uint32_t kx[8], vx[8], fa[8];
@@ -346,20 +368,38 @@ __device__ __forceinline__ void fast_store(const FastRegs<DQK> &rg, const FastCo
     }
 }
 
+// Byte bases and per-thread constants the fast staging needs.
+template <int DQK>
+struct FastCtx {
+    FastConst<DQK> c;
+    const char *kbase, *vbase, *fbase;
+    uint32_t ftile;                 // bytes of RIB rows per tile
+};
+template <int DQK>
+__device__ __forceinline__ FastCtx<DQK> fast_ctx(const Geo &g, int hd, const bf16_t *k, const bf16_t *v, const bf16_t *fk)
+{
+    FastCtx<DQK> x;
+    x.c = fast_const<DQK>(g, hd);
+    x.kbase = (const char *)k;
+    x.vbase = (const char *)v;
+    x.fbase = (const char *)(fk + (int64_t)hd * g.N * g.r);
+    x.ftile = (uint32_t)kFT * (uint32_t)(g.r * 2);
+    return x;
+}
+
+// `rg` holds tile 0 (its global loads were issued by the caller, early).
 template <int DQK, bool ONES>
-__device__ __forceinline__ void attend_fast(const Geo &g, int hd, const int *tok, bf16_t *Kf, bf16_t *Vf,
-                                            const bf16x8 (&Q)[2][DQK / 16], const bf16_t *__restrict__ k,
-                                            const bf16_t *__restrict__ v, const bf16_t *__restrict__ fk,
-                                            f32x16 (&O)[2], float (&lsum)[2])
+__device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx, FastRegs<DQK> &rg, const int *tok,
+                                            bf16_t *Kf, bf16_t *Vf, const bf16x8 (&Q)[2][DQK / 16], f32x16 (&O)[2],
+                                            float (&lsum)[2])
 {
     constexpr int KS = DQK / 16, KSTR = DQK + 8;
     constexpr int KSZ = kFT * KSTR, VSZ = 32 * kFVS;     // bf16 per stage
     const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
     const int ntiles = g.N / kFT;
-    const FastConst<DQK> c = fast_const<DQK>(g, hd);
-    const char *kbase = (const char *)k, *vbase = (const char *)v;
-    const char *fbase = (const char *)(fk + (int64_t)hd * g.N * g.r);
-    const uint32_t ftile = (uint32_t)kFT * (uint32_t)(g.r * 2);
+    const FastConst<DQK> &c = fx.c;
+    const char *kbase = fx.kbase, *vbase = fx.vbase, *fbase = fx.fbase;
+    const uint32_t ftile = fx.ftile;
 
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
@@ -367,12 +407,14 @@ __device__ __forceinline__ void attend_fast(const Geo &g, int hd, const int *tok
         for (int i = 0; i < 16; ++i) O[qb][i] = 0.f;
         lsum[qb] = 0.f;
     }
-
-    FastRegs<DQK> rg;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) fast_load<DQK>(rg, c, g, p, tok, kbase, vbase, fbase);
 #pragma unroll
     for (int p = 0; p < 8; ++p) fast_store<DQK>(rg, c, p, Kf, Vf);
+    {   // tile 1 goes in flight now and is written to LDS at the end of tile 0's block
+        const int t1 = ntiles > 1 ? 1 : 0;
+#pragma unroll
+        for (int p = 0; p < 8; ++p)
+            fast_load<DQK>(rg, c, g, p, tok + t1 * kFT, kbase, vbase, fbase + (uint32_t)t1 * ftile);
+    }
     __syncthreads();
 
     const f32x16 zero = {0};
@@ -380,13 +422,15 @@ __device__ __forceinline__ void attend_fast(const Geo &g, int hd, const int *tok
         const int cur = tile & 1;
         const bf16_t *Kc = Kf + cur * KSZ, *Vc = Vf + cur * VSZ;
         bf16_t *Kn = Kf + (cur ^ 1) * KSZ, *Vn = Vf + (cur ^ 1) * VSZ;
-        const int nt = tile + 1 < ntiles ? tile + 1 : tile;       // the last tile re-stages itself (unused)
+        // `rg` holds tile+1 (requested one block ago); tile+2 is requested at the end of this
+        // block.  Past the end both clamp to the last tile (staged again, never used).
+        const int nt = tile + 2 < ntiles ? tile + 2 : ntiles - 1;
         const int *tokn = tok + nt * kFT;
         const char *fn = fbase + (uint32_t)nt * ftile;
 
         bf16x8 Ak[4][KS], Av[4][2];
         f32x16 S[2];
-        bf16x8 P[2][2];
+        uint4 P[2][2];          // packed bf16 probabilities: B operands of the PV MFMAs
 #pragma unroll
         for (int t = 0; t < KS; ++t) Ak[0][t] = *(const bf16x8 *)(Kc + col * KSTR + 16 * t + 8 * hf);
 #pragma unroll
@@ -415,16 +459,25 @@ __device__ __forceinline__ void attend_fast(const Geo &g, int hd, const int *tok
                             S[ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[kb1][t], Q[qb1][t], S[ns], 0, 0, 0);
                     }
                 } else if (s > 0) {
-                    O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][0], P[ns][0], O[qbp], 0, 0, 0);
+                    O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][0], as_bf16x8(P[ns][0]), O[qbp], 0, 0, 0);
                 }
 #pragma unroll
                 for (int i = 4 * grp; i < 4 * grp + 4; ++i) pe[i] = __builtin_amdgcn_exp2f(S[cs][i]);
-                if (!ONES) lsum[qb] += (pe[4 * grp] + pe[4 * grp + 1]) + (pe[4 * grp + 2] + pe[4 * grp + 3]);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) P[cs][grp >> 1][4 * (grp & 1) + i] = (__bf16)pe[4 * grp + i];
+                // fp32 -> bf16 by truncation: one byte-permute per pair instead of the (slow)
+                // rounding convert.  Numerator and denominator use the same truncated P.
+                const uint32_t w0 = trunc_pack(pe[4 * grp], pe[4 * grp + 1]);
+                const uint32_t w1 = trunc_pack(pe[4 * grp + 2], pe[4 * grp + 3]);
+                if (!ONES) lsum[qb] += (hi_bf16(w0 << 16) + hi_bf16(w0)) + (hi_bf16(w1 << 16) + hi_bf16(w1));
+                if ((grp & 1) == 0) {
+                    P[cs][grp >> 1].x = w0;
+                    P[cs][grp >> 1].y = w1;
+                } else {
+                    P[cs][grp >> 1].z = w0;
+                    P[cs][grp >> 1].w = w1;
+                }
             }
             // group 4: second PV MFMA of the previous block + this step's share of the staging
-            if (s > 0) O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][1], P[ns][1], O[qbp], 0, 0, 0);
+            if (s > 0) O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][1], as_bf16x8(P[ns][1]), O[qbp], 0, 0, 0);
             if (qb == 0 && kb + 1 < 4) {
 #pragma unroll
                 for (int t = 0; t < KS; ++t)
@@ -433,47 +486,20 @@ __device__ __forceinline__ void attend_fast(const Geo &g, int hd, const int *tok
                 for (int t = 0; t < 2; ++t)
                     Av[kb + 1][t] = *(const bf16x8 *)(Vc + col * kFVS + (kb + 1) * 32 + 16 * t + 8 * hf);
             }
-            if (s < 4) {
-                fast_load<DQK>(rg, c, g, 2 * s, tokn, kbase, vbase, fn);
-                fast_load<DQK>(rg, c, g, 2 * s + 1, tokn, kbase, vbase, fn);
-            } else {
+            if (s >= 4) {
                 fast_store<DQK>(rg, c, 2 * (s - 4), Kn, Vn);
                 fast_store<DQK>(rg, c, 2 * (s - 4) + 1, Kn, Vn);
             }
         }
         // drain: PV of the last block
-        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][0], P[1][0], O[1], 0, 0, 0);
-        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][1], P[1][1], O[1], 0, 0, 0);
+        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][0], as_bf16x8(P[1][0]), O[1], 0, 0, 0);
+        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][1], as_bf16x8(P[1][1]), O[1], 0, 0, 0);
+#pragma unroll
+        for (int p = 0; p < 8; ++p) fast_load<DQK>(rg, c, g, p, tokn, kbase, vbase, fn);
 
-        // The order the scheduler is asked to build out of the block above: first the KS
-        // MFMAs of block 0; then, per block, each MFMA followed by its share of exp2 / pack
-        // work, with the operand reads and the staging traffic behind the fifth MFMA.
-        RIB_SG(RIB_SG_DS_RD, KS + 2);
-        RIB_SG(RIB_SG_MFMA, KS);
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const int nm = (s < 7 ? KS : 0) + (s > 0 ? 2 : 0);      // MFMAs issued in this step
-#pragma unroll
-            for (int m = 0; m < 5; ++m) {
-                if (m < nm) RIB_SG(RIB_SG_MFMA, 1);
-                if (m < 4) {
-                    RIB_SG(RIB_SG_TRANS, 4);
-                    RIB_SG(RIB_SG_VALU, ONES ? 2 : 5);
-                } else {
-                    if (nm > 5) RIB_SG(RIB_SG_MFMA, 1);
-                    if ((s & 1) == 0 && s < 6) RIB_SG(RIB_SG_DS_RD, KS + 2);
-                    if (s < 4) {
-                        RIB_SG(RIB_SG_DS_RD, 2);
-                        RIB_SG(RIB_SG_VALU, 4);
-                        RIB_SG(RIB_SG_VMEM_RD, DQK == 64 ? 8 : 6);
-                    } else {
-                        RIB_SG(RIB_SG_VALU, 4);
-                        RIB_SG(RIB_SG_DS_WR, DQK == 64 ? 8 : 6);
-                    }
-                }
-            }
-        }
-        RIB_SG(RIB_SG_MFMA, 2);
+        // The order the scheduler is asked to build out of the block above: every MFMA
+        // followed by its share of the exp2 (transcendental) and pack (VALU) work.
+        sched_pipeline<0, 8 * (DQK / 16 + 2)>();
         __syncthreads();
     }
 }
@@ -495,11 +521,40 @@ template <int DQK, int NT, bool ONES>
 __device__ __forceinline__ void init_fast_tiles(const Geo &g, bf16_t *Kf, bf16_t *Vf)
 {
     constexpr int KSTR = DQK + 8;
-    for (int e = threadIdx.x; e < 2 * kFT * KSTR; e += NT)
-        if (e % KSTR >= g.d + g.r) Kf[e] = 0;
-    for (int e = threadIdx.x; e < 2 * 32 * kFVS; e += NT) {
-        int row = (e % (32 * kFVS)) / kFVS;
-        if (row >= g.d) Vf[e] = (ONES && row == g.d) ? (bf16_t)0x3f80 : (bf16_t)0;
+    const int pad0 = g.d + g.r;                                  // even; columns pad0..DQK-1 are zero
+    for (int row = threadIdx.x; row < 2 * kFT; row += NT)
+        for (int c = pad0; c < DQK; c += 2) *(uint32_t *)(Kf + row * KSTR + c) = 0u;
+    const int vrows = 32 - g.d;                                  // rows d..31 of both stages
+    for (int e = threadIdx.x; e < 2 * vrows * (kFVS / 2); e += NT) {
+        const int per = vrows * (kFVS / 2);
+        const int st = e / per, rem = e - st * per;
+        const int row = g.d + rem / (kFVS / 2), cw = rem - (rem / (kFVS / 2)) * (kFVS / 2);
+        *(uint32_t *)(Vf + (st * 32 + row) * kFVS + 2 * cw) = (ONES && row == g.d) ? 0x3f803f80u : 0u;
+    }
+}
+
+// Token table of window w: entry n = grid token of window-local token n (Sec. 2.2
+// partition after the cyclic shift), -1 for n >= N.  One integer division per thread;
+// the walk from n to n + NT is done with adds and a carry.
+template <int NT>
+__device__ __forceinline__ void fill_tok_table(const Geo &g, int w, int *tok, int count)
+{
+    const int wx = w % g.nwx, t = w / g.nwx, wy = t % g.nwy, b = t / g.nwy;
+    const int sy = NT / g.M, sx = NT - sy * g.M;
+    const int y0 = wy * g.M + g.s, x0 = wx * g.M + g.s;
+    int n = threadIdx.x;
+    int iy = n / g.M, ix = n - iy * g.M;
+    for (; n < count; n += NT) {
+        int y = y0 + iy, x = x0 + ix;
+        if (y >= g.H) y -= g.H;
+        if (x >= g.W) x -= g.W;
+        tok[n] = n < g.N ? (b * g.H + y) * g.W + x : -1;
+        ix += sx;
+        iy += sy;
+        if (ix >= g.M) {
+            ix -= g.M;
+            ++iy;
+        }
     }
 }
 
@@ -527,7 +582,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
     bf16_t *tiles = (bf16_t *)smem;
     bf16_t(*Ka)[kTK * KSTR] = (bf16_t(*)[kTK * KSTR]) tiles;                   // generic layout
     bf16_t(*Vt)[32 * kVStr] = (bf16_t(*)[32 * kVStr])(tiles + Sm::GEN_K);
-    bf16_t *Kf = tiles, *Vf = tiles + Sm::FAST_K;                               // fast layout (same memory)
     int *tok = (int *)(smem + Sm::TILE_BYTES);   // [ntiles*64] grid token of each window-local token, -1 past N
 
     // Workgroups are dealt round-robin to the 8 XCDs; renumber them so that each XCD
@@ -542,7 +596,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
     const int col = lane & 31, hf = lane >> 5;
     const int ntiles = (g.N + kTK - 1) / kTK;
 
-    for (int n = tid; n < ntiles * kTK; n += NT) tok[n] = n < g.N ? (int)grid_token(g, w, n) : -1;
+    fill_tok_table<NT>(g, w, tok, ntiles * kTK);
     init_generic_tiles<DQK, NT, ONES>(g, Ka[0], Vt[0]);
     int foff[St::FP];
 #pragma unroll
@@ -589,13 +643,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
     float mrun[2] = {0.f, 0.f}, lsum[2];
     bool redo = force_max != 0;
     if (!redo) {
-        if (FAST) {
-            init_fast_tiles<DQK, NT, ONES>(g, Kf, Vf);
-            __syncthreads();
-            attend_fast<DQK, ONES>(g, hd, tok, Kf, Vf, Q, k, v, fk, O, lsum);
-        } else {
-            attend<DQK, WAVES, ONES, false>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
-        }
+        attend<DQK, WAVES, ONES, false>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
         bool bad = false;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -604,10 +652,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
             if (!ok && q0 + qb * 32 + col < g.N) bad = true;
         }
         redo = __syncthreads_or(bad);
-        if (FAST && redo) {
-            init_generic_tiles<DQK, NT, ONES>(g, Ka[0], Vt[0]);
-            __syncthreads();
-        }
     }
     if (redo) attend<DQK, WAVES, ONES, true>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
 
@@ -633,6 +677,130 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
     }
 }
 
+// Forward kernel for the common case (whole 128-key tiles, 32-bit byte offsets, r > 0):
+// a prologue with ONE exposed global-memory latency (the first K/V tile and all Q rows
+// are requested together; each wave stages its own 64 Q_aug rows), then attend_fast.
+// Rows whose softmax denominator leaves the safe range send the workgroup through the
+// max-tracking path of the general kernel.
+template <int DQK, bool ONES>
+__global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
+    Geo g, int nqblk, int force_max, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+    const bf16_t *__restrict__ v, const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk,
+    bf16_t *__restrict__ out, float *__restrict__ lse)
+{
+    constexpr int NT = 256, WAVES = 4;
+    constexpr int KS = DQK / 16;
+    constexpr int KSTR = DQK + 8;
+    using St = Stage<DQK, WAVES>;
+    using Sm = FwdSmem<DQK, true>;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    bf16_t *tiles = (bf16_t *)smem;
+    bf16_t *Kf = tiles, *Vf = tiles + Sm::FAST_K;
+    int *tok = (int *)(smem + Sm::TILE_BYTES);
+
+    const int G = gridDim.x, per = G >> 3, rem = G & 7, xcd = blockIdx.x & 7;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    const int64_t u = logical / nqblk;
+    const int blk = logical - (int)(u * nqblk);
+    const int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, hf = lane >> 5;
+
+    fill_tok_table<NT>(g, w, tok, g.N);
+    {   // zero the Q staging area (rows of all four waves): its padding columns must read 0
+        uint4 z = {0u, 0u, 0u, 0u};
+        for (int e = tid; e < NT * KSTR / 8; e += NT) ((uint4 *)tiles)[e] = z;
+    }
+    __syncthreads();
+
+    const FastCtx<DQK> fx = fast_ctx<DQK>(g, hd, k, v, fk);
+    FastRegs<DQK> rg;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) fast_load<DQK>(rg, fx.c, g, p, tok, fx.kbase, fx.vbase, fx.fbase);
+
+    // Q_aug rows of this wave: 16 lanes per token, 4 tokens per pass
+    const int q0 = blk * NT + wave * 64;
+    bf16x8 Q[2][KS];
+    {
+        const float sc = g.scale_c * kLog2e, sp = g.scale_p * kLog2e;
+        const int sub = lane >> 4, j = lane & 15, hp = g.d >> 1, rh = g.r >> 1;
+        const int pair = j < hp ? j : hp - 1;
+        const int f0 = j < rh ? j : rh - 1, f1 = 16 + j < rh ? 16 + j : rh - 1;
+        const char *qbase = (const char *)q;
+        const char *fqb = (const char *)(fq + ((int64_t)hd * g.N + q0) * g.r);
+        uint32_t qx[16], qa[16], qb2[DQK == 64 ? 16 : 1];
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = p * 4 + sub;
+            const uint32_t off = __umul24((uint32_t)tok[q0 + row], fx.c.tsb) + (uint32_t)(hd * g.d + 2 * pair) * 2u;
+            qx[p] = *(const uint32_t *)(qbase + off);
+            const uint32_t frow = (uint32_t)row * (uint32_t)(g.r * 2);
+            qa[p] = *(const uint32_t *)(fqb + frow + 4 * f0);
+            if (DQK == 64) qb2[p] = *(const uint32_t *)(fqb + frow + 4 * f1);
+        }
+        bf16_t *Qs = tiles + wave * 64 * KSTR;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = p * 4 + sub;
+            *(uint32_t *)(Qs + row * KSTR + 2 * pair) = pack_bf16(lo_bf16(qx[p]) * sc, hi_bf16(qx[p]) * sc);
+            *(uint32_t *)(Qs + row * KSTR + g.d + 2 * f0) = pack_bf16(lo_bf16(qa[p]) * sp, hi_bf16(qa[p]) * sp);
+            if (DQK == 64)
+                *(uint32_t *)(Qs + row * KSTR + g.d + 2 * f1) = pack_bf16(lo_bf16(qb2[p]) * sp, hi_bf16(qb2[p]) * sp);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int t = 0; t < KS; ++t) Q[qb][t] = *(const bf16x8 *)(Qs + (qb * 32 + col) * KSTR + 16 * t + 8 * hf);
+        __syncthreads();
+    }
+
+    f32x16 O[2];
+    float mrun[2] = {0.f, 0.f}, lsum[2];
+    bool redo = force_max != 0;
+    if (!redo) {
+        init_fast_tiles<DQK, NT, ONES>(g, Kf, Vf);
+        attend_fast<DQK, ONES>(g, fx, rg, tok, Kf, Vf, Q, O, lsum);
+        bool bad = false;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            float l = ONES ? ones_row(O[qb], g.d) : lsum[qb] + __shfl_xor(lsum[qb], 32);
+            if (!((l >= 0x1p-60f) && (l <= 0x1p60f))) bad = true;
+        }
+        redo = __syncthreads_or(bad);
+    }
+    if (redo) {
+        bf16_t(*Ka)[kTK * KSTR] = (bf16_t(*)[kTK * KSTR]) tiles;
+        bf16_t(*Vt)[32 * kVStr] = (bf16_t(*)[32 * kVStr])(tiles + Sm::GEN_K);
+        int foff[St::FP];
+#pragma unroll
+        for (int p = 0; p < St::FP; ++p) {
+            int e = p * NT + tid, hr = g.r >> 1;
+            int tk = e / hr;
+            foff[p] = tk * KSTR + g.d + 2 * (e - tk * hr);
+        }
+        __syncthreads();
+        init_generic_tiles<DQK, NT, ONES>(g, Ka[0], Vt[0]);
+        __syncthreads();
+        attend<DQK, WAVES, ONES, true>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
+    }
+
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const float l = ONES ? ones_row(O[qb], g.d) : lsum[qb] + __shfl_xor(lsum[qb], 32);
+        const int n = q0 + qb * 32 + col;
+        const float inv = 1.f / l;
+        bf16_t *dst = out + (int64_t)tok[n] * g.C + hd * g.d;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            int dv = 8 * (i >> 2) + 4 * hf + (i & 3);
+            if (dv < g.d) *(uint32_t *)(dst + dv) = pack_bf16(O[qb][i] * inv, O[qb][i + 1] * inv);
+        }
+        if (lse != nullptr && hf == 0)
+            lse[u * g.N + n] = (mrun[qb] + __builtin_amdgcn_logf(l) + (redo ? 0.f : kTruncLog2)) * kLn2;
+    }
+}
+
 template <int DQK, bool ONES, bool FAST>
 hipError_t launch(const Geo &g, int force_max, const void *q, const void *k, const void *v, const void *fq,
                   const void *fk, void *out, float *lse, hipStream_t st)
@@ -641,16 +809,17 @@ hipError_t launch(const Geo &g, int force_max, const void *q, const void *k, con
     const int nqblk = (g.N + WAVES * 64 - 1) / (WAVES * 64);
     const int ntiles = (g.N + kTK - 1) / kTK;
     const size_t dyn = FwdSmem<DQK, FAST>::TILE_BYTES + (size_t)ntiles * kTK * sizeof(int);
+    if (dyn > (size_t)kMaxDynLds) return hipErrorInvalidValue;
+    auto kern = FAST ? mfma_fwd_fast_kernel<DQK, ONES> : mfma_fwd_kernel<DQK, WAVES, ONES, false>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void *)mfma_fwd_kernel<DQK, WAVES, ONES, FAST>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+    std::call_once(once, [kern] {
+        attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
     });
     if (attr_err != hipSuccess) return attr_err;
-    hipLaunchKernelGGL((mfma_fwd_kernel<DQK, WAVES, ONES, FAST>), dim3((unsigned)(g.units * nqblk)),
-                       dim3(WAVES * 64), dyn, st, g, nqblk, force_max, (const bf16_t *)q, (const bf16_t *)k,
-                       (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk, (bf16_t *)out, lse);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(g.units * nqblk)), dim3(WAVES * 64), dyn, st, g, nqblk, force_max,
+                       (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq,
+                       (const bf16_t *)fk, (bf16_t *)out, lse);
     return hipGetLastError();
 }
 

@@ -56,6 +56,31 @@ __device__ __forceinline__ int64_t grid_token(const Geo &g, int w, int n)
     return ((int64_t)b * g.H + y) * g.W + x;
 }
 
+// Token table of window w: entry n = grid token of window-local token n (Sec. 2.2
+// partition after the cyclic shift), -1 for n >= N.  One integer division per thread;
+// the walk from n to n + NT is done with adds and a carry.
+template <int NT>
+__device__ __forceinline__ void fill_tok_table(const Geo &g, int w, int *tok, int count)
+{
+    const int wx = w % g.nwx, t = w / g.nwx, wy = t % g.nwy, b = t / g.nwy;
+    const int sy = NT / g.M, sx = NT - sy * g.M;
+    const int y0 = wy * g.M + g.s, x0 = wx * g.M + g.s;
+    int n = threadIdx.x;
+    int iy = n / g.M, ix = n - iy * g.M;
+    for (; n < count; n += NT) {
+        int y = y0 + iy, x = x0 + ix;
+        if (y >= g.H) y -= g.H;
+        if (x >= g.W) x -= g.W;
+        tok[n] = n < g.N ? (b * g.H + y) * g.W + x : -1;
+        ix += sx;
+        iy += sy;
+        if (ix >= g.M) {
+            ix -= g.M;
+            ++iy;
+        }
+    }
+}
+
 // Launchers (each returns the hipError_t of its launches).
 hipError_t launch_valu_fwd(const Geo &g, int dtype, const void *q, const void *k, const void *v,
                            const void *fq, const void *fk, void *out, float *lse, hipStream_t st);

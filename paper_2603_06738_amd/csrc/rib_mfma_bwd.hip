@@ -487,6 +487,447 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
     }
 }
 
+// =======================================================================================
+// Fast path (whole 256-token blocks, 32-bit byte offsets, r > 0).  Same mathematics and LDS
+// images as the kernels above; what changes is the plumbing around the MFMA loop:
+//   - one exposed global-memory latency in the prologue: the first streamed tile and all
+//     stationary rows are requested together, and each wave stages its own 64 stationary
+//     rows (no workgroup-wide rounds);
+//   - streamed tiles are requested two tiles ahead (the loads for tile t+2 are issued at
+//     the end of tile t's block and land in LDS at the end of tile t+1's block);
+//   - staging has no predicates (idle lanes duplicate a neighbour), builds byte offsets
+//     with one 24-bit multiply-add, and writes the transposed images four tokens at a time;
+//   - P and dS go to bf16 by truncation (one byte-permute per pair instead of the slow
+//     rounding convert); the mean loss of truncation is multiplied back into the results.
+constexpr float kTruncGain = 1.0028176f;   // 1 + 2^-8 / (2 ln 2): mean relative loss of bf16 truncation
+
+__device__ __forceinline__ uint32_t trunc_pack(float lo, float hi)
+{
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d)
+{
+    uint4 w = {a, b, c, d};
+    return __builtin_bit_cast(bf16x8, w);
+}
+
+template <int DQK, int DVK>
+struct FRegs {
+    uint32_t xc[4], yc[4], fa[4], fb[DQK == 64 ? 4 : 1];
+    float e0, e1;
+};
+
+template <int DQK, int DVK>
+struct FConst {
+    uint32_t lane_c, tsb, dsb;      // channel-pair byte offset in a token; strided / dense token stride in bytes
+    uint32_t f_off0, f_off1, frow;  // byte offsets of this lane's RIB dwords; bytes per RIB row
+    int tok_idx;                    // first of this lane's 4 tokens in a tile
+    int xr, xt, yr, yt, fr0, ft0, fr1, ft1;   // bf16 element offsets inside a stage
+};
+
+template <int DQK, int DVK>
+__device__ __forceinline__ FConst<DQK, DVK> fconst(const Geo &g, int hd)
+{
+    using L = Lay<DQK, DVK>;
+    FConst<DQK, DVK> c;
+    const int tid = threadIdx.x, grp = tid >> 4, j = tid & 15;
+    const int hp = g.d >> 1, rh = g.r >> 1;
+    const int pair = j < hp ? j : hp - 1;
+    const int f0 = j < rh ? j : rh - 1, f1 = 16 + j < rh ? 16 + j : rh - 1;
+    const int pc = perm_col(grp * 4);
+    c.lane_c = (uint32_t)(hd * g.d + 2 * pair) * 2u;
+    c.tsb = (uint32_t)g.tstride * 2u;
+    c.dsb = (uint32_t)g.C * 2u;
+    c.f_off0 = (uint32_t)f0 * 4u;
+    c.f_off1 = (uint32_t)f1 * 4u;
+    c.frow = (uint32_t)g.r * 2u;
+    c.tok_idx = grp * 4;
+    c.xr = L::XR + grp * 4 * L::XS + 2 * pair;
+    c.xt = L::XT + (2 * pair) * kTS + pc;
+    c.yr = L::YR + grp * 4 * L::YS + 2 * pair;
+    c.yt = L::YT + (2 * pair) * kTS + pc;
+    c.fr0 = L::XR + grp * 4 * L::XS + g.d + 2 * f0;
+    c.ft0 = L::XT + (g.d + 2 * f0) * kTS + pc;
+    c.fr1 = L::XR + grp * 4 * L::XS + g.d + 2 * f1;
+    c.ft1 = L::XT + (g.d + 2 * f1) * kTS + pc;
+    return c;
+}
+
+// Request tile `tile` of the streamed operand pair.  QDO: X = q (strided), Y = dO (dense),
+// extras = LSE, delta.  Otherwise X = k, Y = v (both strided).
+template <int DQK, int DVK, bool QDO>
+__device__ __forceinline__ void fload(FRegs<DQK, DVK> &rg, const FConst<DQK, DVK> &c, const Geo &g, int64_t u, int tile,
+                                      const int *tok, const char *xb, const char *yb, const char *fbase,
+                                      const float *__restrict__ lse, const float *__restrict__ delta)
+{
+    const char *fb = fbase + (uint32_t)tile * (uint32_t)kT * c.frow;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t t = (uint32_t)tok[tile * kT + c.tok_idx + p];
+        rg.xc[p] = *(const uint32_t *)(xb + (__umul24(t, c.tsb) + c.lane_c));
+        rg.yc[p] = *(const uint32_t *)(yb + (__umul24(t, QDO ? c.dsb : c.tsb) + c.lane_c));
+        const uint32_t row = (uint32_t)(c.tok_idx + p) * c.frow;
+        rg.fa[p] = *(const uint32_t *)(fb + row + c.f_off0);
+        if (DQK == 64) rg.fb[p] = *(const uint32_t *)(fb + row + c.f_off1);
+    }
+    if (QDO && threadIdx.x < kT) {
+        rg.e0 = lse[u * g.N + tile * kT + threadIdx.x];
+        rg.e1 = delta[u * g.N + tile * kT + threadIdx.x];
+    }
+}
+
+// four dwords (tokens t..t+3, one channel pair) -> the two transposed rows, 8 bytes each
+__device__ __forceinline__ void store_t4(bf16_t *dst, const uint32_t (&w)[4])
+{
+    uint2 even, odd;
+    even.x = __builtin_amdgcn_perm(w[1], w[0], 0x05040100u);
+    even.y = __builtin_amdgcn_perm(w[3], w[2], 0x05040100u);
+    odd.x = __builtin_amdgcn_perm(w[1], w[0], 0x07060302u);
+    odd.y = __builtin_amdgcn_perm(w[3], w[2], 0x07060302u);
+    *(uint2 *)dst = even;
+    *(uint2 *)(dst + kTS) = odd;
+}
+
+template <int DQK, int DVK, bool QDO, bool TRANS_Y>
+__device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<DQK, DVK> &c, bf16_t *S, float sc, float sp)
+{
+    using L = Lay<DQK, DVK>;
+    uint32_t x[4], fa[4], fb[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        x[p] = rg.xc[p];
+        fa[p] = rg.fa[p];
+        fb[p] = DQK == 64 ? rg.fb[p] : 0u;
+        if (QDO) {
+            x[p] = pack_bf16(lo_bf16(x[p]) * sc, hi_bf16(x[p]) * sc);
+            fa[p] = pack_bf16(lo_bf16(fa[p]) * sp, hi_bf16(fa[p]) * sp);
+            if (DQK == 64) fb[p] = pack_bf16(lo_bf16(fb[p]) * sp, hi_bf16(fb[p]) * sp);
+        }
+        *(uint32_t *)(S + c.xr + p * L::XS) = x[p];
+        *(uint32_t *)(S + c.yr + p * L::YS) = rg.yc[p];
+        *(uint32_t *)(S + c.fr0 + p * L::XS) = fa[p];
+        if (DQK == 64) *(uint32_t *)(S + c.fr1 + p * L::XS) = fb[p];
+    }
+    store_t4(S + c.xt, x);
+    store_t4(S + c.ft0, fa);
+    if (DQK == 64) store_t4(S + c.ft1, fb);
+    if (TRANS_Y) store_t4(S + c.yt, rg.yc);
+    if (threadIdx.x < kT) {
+        uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
+        if (QDO) {
+            ex = split_bf16(-rg.e0 * kLog2e);
+            ey = split_bf16(-rg.e1);
+        }
+        *(uint32_t *)(S + L::XR + threadIdx.x * L::XS + DQK - 2) = ex;
+        *(uint32_t *)(S + L::YR + threadIdx.x * L::YS + DVK - 2) = ey;
+    }
+}
+
+// Each wave stages its own 64 stationary rows (X rows [64][XS], Y rows [64][YS], extras
+// included) into its private LDS area `W` and reads them back as MFMA B operands.
+template <int DQK, int DVK, bool QDO>
+__device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u, int n0, const int *tok, const char *xb,
+                                                const char *yb, const bf16_t *f, const float *__restrict__ lse,
+                                                const float *__restrict__ delta, float sc, float sp, bf16_t *W,
+                                                bf16x8 (&Xb)[2][DQK / 16], bf16x8 (&Yb)[2][DVK / 16])
+{
+    using L = Lay<DQK, DVK>;
+    const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15, col = lane & 31, hf = lane >> 5;
+    const int hp = g.d >> 1, rh = g.r >> 1;
+    const int pair = j < hp ? j : hp - 1;
+    const int f0 = j < rh ? j : rh - 1, f1 = 16 + j < rh ? 16 + j : rh - 1;
+    const uint32_t lane_c = (uint32_t)(hd * g.d + 2 * pair) * 2u;
+    const uint32_t tsb = (uint32_t)g.tstride * 2u, ysb = QDO ? (uint32_t)g.C * 2u : tsb, frow = (uint32_t)g.r * 2u;
+    const char *fb = (const char *)(f + ((int64_t)hd * g.N + n0) * g.r);
+    bf16_t *Xs = W, *Ys = W + kT * L::XS;
+    uint32_t xx[16], yy[16], fa[16], fb2[DQK == 64 ? 16 : 1];
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const int row = p * 4 + sub;
+        const uint32_t t = (uint32_t)tok[n0 + row];
+        xx[p] = *(const uint32_t *)(xb + (__umul24(t, tsb) + lane_c));
+        yy[p] = *(const uint32_t *)(yb + (__umul24(t, ysb) + lane_c));
+        fa[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f0);
+        if (DQK == 64) fb2[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f1);
+    }
+    float e0 = 0.f, e1 = 0.f;
+    if (QDO) {
+        e0 = lse[u * g.N + n0 + lane];
+        e1 = delta[u * g.N + n0 + lane];
+    }
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const int row = p * 4 + sub;
+        uint32_t a = xx[p], b = fa[p], b2 = DQK == 64 ? fb2[p] : 0u;
+        if (QDO) {
+            a = pack_bf16(lo_bf16(a) * sc, hi_bf16(a) * sc);
+            b = pack_bf16(lo_bf16(b) * sp, hi_bf16(b) * sp);
+            if (DQK == 64) b2 = pack_bf16(lo_bf16(b2) * sp, hi_bf16(b2) * sp);
+        }
+        *(uint32_t *)(Xs + row * L::XS + 2 * pair) = a;
+        *(uint32_t *)(Xs + row * L::XS + g.d + 2 * f0) = b;
+        if (DQK == 64) *(uint32_t *)(Xs + row * L::XS + g.d + 2 * f1) = b2;
+        *(uint32_t *)(Ys + row * L::YS + 2 * pair) = yy[p];
+    }
+    {
+        uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
+        if (QDO) {
+            ex = split_bf16(-e0 * kLog2e);
+            ey = split_bf16(-e1);
+        }
+        *(uint32_t *)(Xs + lane * L::XS + DQK - 2) = ex;
+        *(uint32_t *)(Ys + lane * L::YS + DVK - 2) = ey;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        read_rows<DQK / 16>(Xb[b], Xs, L::XS, b * 32 + col, hf);
+        read_rows<DVK / 16>(Yb[b], Ys, L::YS, b * 32 + col, hf);
+    }
+    __syncthreads();
+}
+
+template <int DQK, int DVK>
+struct FSmem {
+    using L = Lay<DQK, DVK>;
+    static constexpr int STAT = kWaves * (kT * L::XS + kT * L::YS);            // stationary staging, bf16
+    static constexpr int ELEMS = (2 * L::STAGE > STAT ? 2 * L::STAGE : STAT);
+    static constexpr int ELEMS16 = (ELEMS + 7) / 8 * 8;
+    static constexpr size_t BYTES = (size_t)ELEMS16 * sizeof(bf16_t);
+};
+
+__device__ __forceinline__ void zero_lds(bf16_t *base, int elems16)
+{
+    const uint4 z = {0u, 0u, 0u, 0u};
+    for (int e = threadIdx.x; e < elems16 / 8; e += kNT) ((uint4 *)base)[e] = z;
+}
+
+__device__ __forceinline__ void block_coords(const Geo &g, int nblk, int64_t &u, int &blk, int &w, int &hd)
+{
+    const int G = gridDim.x, per = G >> 3, rem = G & 7, xcd = blockIdx.x & 7;
+    const int logical = xcd * per + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
+    u = logical / nblk;
+    blk = logical - (int)(u * nblk);
+    w = (int)(u / g.heads);
+    hd = (int)(u - (int64_t)w * g.heads);
+}
+
+// dQ (+ dF_q partial), fast path.
+template <int DQK, int DVK>
+__global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dq_fast_kernel(
+    Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
+    const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dq, float *__restrict__ dfq_part)
+{
+    using L = Lay<DQK, DVK>;
+    using Sm = FSmem<DQK, DVK>;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
+    int *tok = (int *)(smem + Sm::ELEMS16);
+
+    int64_t u;
+    int blk, w, hd;
+    block_coords(g, nblk, u, blk, w, hd);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int ntiles = g.N / kT;
+    const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
+
+    fill_tok_table<kNT>(g, w, tok, g.N);
+    zero_lds(smem, Sm::ELEMS16);
+    __syncthreads();
+
+    const FConst<DQK, DVK> c = fconst<DQK, DVK>(g, hd);
+    const char *kb = (const char *)k, *vb = (const char *)v;
+    const char *fkb = (const char *)(fk + (int64_t)hd * g.N * g.r);
+    FRegs<DQK, DVK> rg;
+    fload<DQK, DVK, false>(rg, c, g, u, 0, tok, kb, vb, fkb, lse, delta);
+
+    const int q0 = (blk * kWaves + wave) * kT;
+    bf16x8 Qb[2][L::KS], Gb[2][L::VS];
+    stationary_rows<DQK, DVK, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
+                                    smem + wave * (kT * L::XS + kT * L::YS), Qb, Gb);
+    zero_lds(smem, Sm::ELEMS16);
+    __syncthreads();
+    fstore<DQK, DVK, false, false>(rg, c, stage0, 1.f, 1.f);
+    fload<DQK, DVK, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
+    __syncthreads();
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[qb][mb][i] = 0.f;
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
+#pragma unroll
+        for (int kb2 = 0; kb2 < 2; ++kb2) {
+            bf16x8 Ak[L::KS], Av[L::VS], At[2][2];
+            read_rows<L::KS>(Ak, cur + L::XR, L::XS, kb2 * 32 + col, hf);
+            read_rows<L::VS>(Av, cur + L::YR, L::YS, kb2 * 32 + col, hf);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    At[mb][t] = *(const bf16x8 *)(cur + L::XT + (32 * mb + col) * kTS + kb2 * 32 + 16 * t + 8 * hf);
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                f32x16 S = {0}, D = {0};
+#pragma unroll
+                for (int t = 0; t < L::KS; ++t) S = mfma(Ak[t], Qb[qb][t], S);
+#pragma unroll
+                for (int t = 0; t < L::VS; ++t) D = mfma(Av[t], Gb[qb][t], D);
+                uint32_t wds[8];
+#pragma unroll
+                for (int i = 0; i < 16; i += 2)
+                    wds[i >> 1] = trunc_pack(__builtin_amdgcn_exp2f(S[i]) * D[i], __builtin_amdgcn_exp2f(S[i + 1]) * D[i + 1]);
+                const bf16x8 B0 = as_bf16x8(wds[0], wds[1], wds[2], wds[3]);
+                const bf16x8 B1 = as_bf16x8(wds[4], wds[5], wds[6], wds[7]);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    acc[qb][mb] = mfma(At[mb][0], B0, acc[qb][mb]);
+                    acc[qb][mb] = mfma(At[mb][1], B1, acc[qb][mb]);
+                }
+            }
+        }
+        fstore<DQK, DVK, false, false>(rg, c, nxt, 1.f, 1.f);
+        fload<DQK, DVK, false>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, kb, vb, fkb, lse, delta);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int n = q0 + qb * 32 + col;
+        bf16_t *gd = dq + (int64_t)tok[n] * g.C + hd * g.d;
+        float *pd = dfq_part + (u * g.N + n) * g.r;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+            store_aug(acc[qb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain, gd, pd);
+    }
+}
+
+// dK, dV (+ dF_k partial), fast path.
+template <int DQK, int DVK>
+__global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dkv_fast_kernel(
+    Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
+    const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
+    const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
+    float *__restrict__ dfk_part)
+{
+    using L = Lay<DQK, DVK>;
+    using Sm = FSmem<DQK, DVK>;
+    extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
+    bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
+    int *tok = (int *)(smem + Sm::ELEMS16);
+
+    int64_t u;
+    int blk, w, hd;
+    block_coords(g, nblk, u, blk, w, hd);
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int ntiles = g.N / kT;
+    const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
+
+    fill_tok_table<kNT>(g, w, tok, g.N);
+    zero_lds(smem, Sm::ELEMS16);
+    __syncthreads();
+
+    const FConst<DQK, DVK> c = fconst<DQK, DVK>(g, hd);
+    const char *qb_ = (const char *)q, *gb_ = (const char *)dout;
+    const char *fqb = (const char *)(fq + (int64_t)hd * g.N * g.r);
+    FRegs<DQK, DVK> rg;
+    fload<DQK, DVK, true>(rg, c, g, u, 0, tok, qb_, gb_, fqb, lse, delta);
+
+    const int k0 = (blk * kWaves + wave) * kT;
+    bf16x8 Kb[2][L::KS], Vb[2][L::VS];
+    stationary_rows<DQK, DVK, false>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, 1.f, 1.f,
+                                     smem + wave * (kT * L::XS + kT * L::YS), Kb, Vb);
+    zero_lds(smem, Sm::ELEMS16);
+    __syncthreads();
+    fstore<DQK, DVK, true, true>(rg, c, stage0, sc2, sp2);
+    fload<DQK, DVK, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
+    __syncthreads();
+
+    f32x16 accV[2], accK[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) accV[kb][i] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) accK[kb][mb][i] = 0.f;
+    }
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            bf16x8 Aq[L::KS], Ag[L::VS], Aqt[2][2], Agt[2];
+            read_rows<L::KS>(Aq, cur + L::XR, L::XS, qb * 32 + col, hf);
+            read_rows<L::VS>(Ag, cur + L::YR, L::YS, qb * 32 + col, hf);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                Agt[t] = *(const bf16x8 *)(cur + L::YT + col * kTS + qb * 32 + 16 * t + 8 * hf);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    Aqt[mb][t] = *(const bf16x8 *)(cur + L::XT + (32 * mb + col) * kTS + qb * 32 + 16 * t + 8 * hf);
+            }
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                f32x16 S = {0}, D = {0};
+#pragma unroll
+                for (int t = 0; t < L::KS; ++t) S = mfma(Aq[t], Kb[kb][t], S);
+#pragma unroll
+                for (int t = 0; t < L::VS; ++t) D = mfma(Ag[t], Vb[kb][t], D);
+                uint32_t wp[8], wds[8];
+#pragma unroll
+                for (int i = 0; i < 16; i += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(S[i]), p1 = __builtin_amdgcn_exp2f(S[i + 1]);
+                    wp[i >> 1] = trunc_pack(p0, p1);
+                    wds[i >> 1] = trunc_pack(p0 * D[i], p1 * D[i + 1]);
+                }
+                accV[kb] = mfma(Agt[0], as_bf16x8(wp[0], wp[1], wp[2], wp[3]), accV[kb]);
+                accV[kb] = mfma(Agt[1], as_bf16x8(wp[4], wp[5], wp[6], wp[7]), accV[kb]);
+                const bf16x8 B0 = as_bf16x8(wds[0], wds[1], wds[2], wds[3]);
+                const bf16x8 B1 = as_bf16x8(wds[4], wds[5], wds[6], wds[7]);
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) {
+                    accK[kb][mb] = mfma(Aqt[mb][0], B0, accK[kb][mb]);
+                    accK[kb][mb] = mfma(Aqt[mb][1], B1, accK[kb][mb]);
+                }
+            }
+        }
+        fstore<DQK, DVK, true, true>(rg, c, nxt, sc2, sp2);
+        fload<DQK, DVK, true>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, qb_, gb_, fqb, lse, delta);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        const int n = k0 + kb * 32 + col;
+        const int64_t base = (int64_t)tok[n] * g.C + hd * g.d;
+        float *pd = dfk_part + (u * g.N + n) * g.r;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+            store_aug(accK[kb][mb], mb, hf, g, kLn2 * kTruncGain, kLn2 * kTruncGain, dk + base, pd);
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+            int cc = 8 * (i >> 2) + 4 * hf + (i & 3);
+            if (cc < g.d)
+                *(uint32_t *)(dv + base + cc) = pack_bf16(accV[kb][i] * kTruncGain, accV[kb][i + 1] * kTruncGain);
+        }
+    }
+}
+
+static bool bwd_fast_ok(const Geo &g)
+{
+    const int64_t tokens = (int64_t)g.B * g.H * g.W;
+    return g.r > 0 && g.N % (kWaves * kT) == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+           tokens * g.tstride * 2 < ((int64_t)1 << 32);
+}
+
 template <int DQK, int DVK>
 hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
                   const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv, float *dfq,
@@ -500,28 +941,32 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     hipError_t e = launch_delta(g, RIB_BF16, out, dout, delta, st);
     if (e != hipSuccess) return e;
 
+    const bool fast = bwd_fast_ok(g);
     const int ntiles = (g.N + kT - 1) / kT;
     const int nblk = (ntiles + kWaves - 1) / kWaves;
-    const size_t smem = (size_t)2 * L::STAGE * sizeof(bf16_t) + (size_t)ntiles * kT * sizeof(int);
+    const size_t tiles_bytes = fast ? FSmem<DQK, DVK>::BYTES : (size_t)2 * L::STAGE * sizeof(bf16_t);
+    const size_t smem = tiles_bytes + (size_t)ntiles * kT * sizeof(int);
+    if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dq_kernel<DQK, DVK>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+        const void *ks[4] = {(const void *)mfma_bwd_dq_kernel<DQK, DVK>, (const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
+                             (const void *)mfma_bwd_dq_fast_kernel<DQK, DVK>,
+                             (const void *)mfma_bwd_dkv_fast_kernel<DQK, DVK>};
+        for (int i = 0; i < 4 && attr_err == hipSuccess; ++i)
+            attr_err = hipFuncSetAttribute(ks[i], hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
     });
     if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(g.units * nblk)), block(kNT);
-    hipLaunchKernelGGL((mfma_bwd_dkv_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
-                       (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,
-                       (const bf16_t *)dout, lse, delta, (bf16_t *)dk, (bf16_t *)dv, pk);
+    auto kdkv = fast ? mfma_bwd_dkv_fast_kernel<DQK, DVK> : mfma_bwd_dkv_kernel<DQK, DVK>;
+    auto kdq = fast ? mfma_bwd_dq_fast_kernel<DQK, DVK> : mfma_bwd_dq_kernel<DQK, DVK>;
+    hipLaunchKernelGGL(kdkv, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dk,
+                       (bf16_t *)dv, pk);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((mfma_bwd_dq_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
-                       (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,
-                       (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
+    hipLaunchKernelGGL(kdq, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_reduce_df(g, pq, pk, dfq, dfk, st);

@@ -533,31 +533,6 @@ __device__ __forceinline__ void init_fast_tiles(const Geo &g, bf16_t *Kf, bf16_t
     }
 }
 
-// Token table of window w: entry n = grid token of window-local token n (Sec. 2.2
-// partition after the cyclic shift), -1 for n >= N.  One integer division per thread;
-// the walk from n to n + NT is done with adds and a carry.
-template <int NT>
-__device__ __forceinline__ void fill_tok_table(const Geo &g, int w, int *tok, int count)
-{
-    const int wx = w % g.nwx, t = w / g.nwx, wy = t % g.nwy, b = t / g.nwy;
-    const int sy = NT / g.M, sx = NT - sy * g.M;
-    const int y0 = wy * g.M + g.s, x0 = wx * g.M + g.s;
-    int n = threadIdx.x;
-    int iy = n / g.M, ix = n - iy * g.M;
-    for (; n < count; n += NT) {
-        int y = y0 + iy, x = x0 + ix;
-        if (y >= g.H) y -= g.H;
-        if (x >= g.W) x -= g.W;
-        tok[n] = n < g.N ? (b * g.H + y) * g.W + x : -1;
-        ix += sx;
-        iy += sy;
-        if (ix >= g.M) {
-            ix -= g.M;
-            ++iy;
-        }
-    }
-}
-
 template <int DQK, bool FAST>
 struct FwdSmem {
     static constexpr int KSTR = DQK + 8;

@@ -155,7 +155,30 @@ __global__ __launch_bounds__(kThreads) void valu_fwd_kernel(Geo g, int nblk, con
 // delta[u][i] = dO[i] . O[i] over the head's channels.  Sixteen lanes share one
 // (token, head): consecutive groups are the heads of one token, so a wave reads whole
 // contiguous token rows of O and dO; each lane multiplies its share of the d channels
-// and the group adds up with lane shuffles.
+// (a pair per load where alignment allows) and the group adds up with lane shuffles.
+template <typename T>
+__device__ __forceinline__ float dot_share(const T *a, const T *b, int d, int sub)
+{
+    float acc = 0.f;
+    for (int t = sub; t < d; t += 16) acc = fmaf(widen(a[t]), widen(b[t]), acc);
+    return acc;
+}
+template <>
+__device__ __forceinline__ float dot_share<bf16_t>(const bf16_t *a, const bf16_t *b, int d, int sub)
+{
+    float acc = 0.f;
+    if (((d & 1) == 0) && ((((uintptr_t)a | (uintptr_t)b) & 3) == 0)) {      // dword pairs
+        for (int t = 2 * sub; t < d; t += 32) {
+            const uint32_t x = *(const uint32_t *)(a + t), y = *(const uint32_t *)(b + t);
+            acc = fmaf(__uint_as_float(x << 16), __uint_as_float(y << 16), acc);
+            acc = fmaf(__uint_as_float(x & 0xffff0000u), __uint_as_float(y & 0xffff0000u), acc);
+        }
+    } else {
+        for (int t = sub; t < d; t += 16) acc = fmaf(widen(a[t]), widen(b[t]), acc);
+    }
+    return acc;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, const T *__restrict__ out,
                                                               const T *__restrict__ dout, float *__restrict__ delta)
@@ -172,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, const T *__
         w = wn / g.N;
         n = (int)(wn - w * g.N);
         const int64_t base = grid_token(g, (int)w, n) * g.C + hd * g.d;
-        for (int t = sub; t < g.d; t += 16) acc = fmaf(widen(out[base + t]), widen(dout[base + t]), acc);
+        acc = dot_share<T>(out + base, dout + base, g.d, sub);
     }
 #pragma unroll
     for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
@@ -332,8 +355,19 @@ __global__ __launch_bounds__(kThreads) void reduce_df_kernel(Geo g, const float 
     const float *src = blockIdx.y == 0 ? part_q : part_k;
     float *dst = blockIdx.y == 0 ? dfq : dfk;
     const int64_t nwin = g.units / g.heads;
+    const int64_t step = (int64_t)g.heads * per_head;
+    const float *p = src + (int64_t)hd * per_head + e;
+    // fixed order (ascending windows); eight loads in flight per lane
     float acc = 0.f;
-    for (int64_t w = 0; w < nwin; ++w) acc += src[(w * g.heads + hd) * per_head + e];
+    int64_t w = 0;
+    for (; w + 8 <= nwin; w += 8) {
+        float t[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = p[(w + i) * step];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc += t[i];
+    }
+    for (; w < nwin; ++w) acc += p[w * step];
     dst[idx] = acc;
 }
 

@@ -179,27 +179,34 @@ __device__ __forceinline__ float dot_share<bf16_t>(const bf16_t *a, const bf16_t
     return acc;
 }
 
+// One workgroup = 64 consecutive window-local tokens of one window, all heads: the grid
+// tokens are computed once (one division per token) and kept in LDS; then sixteen lanes
+// share a (token, head) and walk heads in the outer and tokens in the inner loop.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, const T *__restrict__ out,
+__global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, int nchunk, const T *__restrict__ out,
                                                               const T *__restrict__ dout, float *__restrict__ delta)
 {
-    const int64_t grp = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 4;   // (w*N + n)*heads + hd
-    const int sub = threadIdx.x & 15;
-    const int64_t total = g.units * g.N;
-    float acc = 0.f;
-    int hd = 0, n = 0;
-    int64_t w = 0;
-    if (grp < total) {
-        hd = (int)(grp % g.heads);
-        const int64_t wn = grp / g.heads;
-        w = wn / g.N;
-        n = (int)(wn - w * g.N);
-        const int64_t base = grid_token(g, (int)w, n) * g.C + hd * g.d;
-        acc = dot_share<T>(out + base, dout + base, g.d, sub);
-    }
+    __shared__ int64_t tok[64];
+    const int w = blockIdx.x / nchunk;
+    const int n0 = (blockIdx.x - w * nchunk) * 64;
+    const int tid = threadIdx.x, grp = tid >> 4, sub = tid & 15;
+    if (tid < 64) tok[tid] = n0 + tid < g.N ? grid_token(g, w, n0 + tid) : -1;
+    __syncthreads();
+    for (int hd = 0; hd < g.heads; ++hd) {
 #pragma unroll
-    for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-    if (grp < total && sub == 0) delta[(w * g.heads + hd) * g.N + n] = acc;
+        for (int it = 0; it < 4; ++it) {
+            const int nl = it * 16 + grp;
+            const int64_t t = tok[nl];
+            float acc = 0.f;
+            if (t >= 0) {
+                const int64_t base = t * g.C + hd * g.d;
+                acc = dot_share<T>(out + base, dout + base, g.d, sub);
+            }
+#pragma unroll
+            for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+            if (t >= 0 && sub == 0) delta[((int64_t)w * g.heads + hd) * g.N + n0 + nl] = acc;
+        }
+    }
 }
 
 // dQ and this unit's dF_q contribution: rows are queries, tiles are keys.
@@ -440,13 +447,14 @@ BwdWs bwd_ws_layout(const Geo &g)
 
 hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *dout, float *delta, hipStream_t st)
 {
-    const int64_t rows = g.units * g.N;
-    dim3 grid((unsigned)((rows * 16 + kThreads - 1) / kThreads));
+    const int nchunk = (g.N + 63) / 64;
+    const int64_t nwin = g.units / g.heads;
+    dim3 grid((unsigned)(nwin * nchunk));
     if (dtype == RIB_BF16)
-        hipLaunchKernelGGL((valu_delta_kernel<bf16_t>), grid, dim3(kThreads), 0, st, g, (const bf16_t *)out,
+        hipLaunchKernelGGL((valu_delta_kernel<bf16_t>), grid, dim3(kThreads), 0, st, g, nchunk, (const bf16_t *)out,
                            (const bf16_t *)dout, delta);
     else
-        hipLaunchKernelGGL((valu_delta_kernel<float>), grid, dim3(kThreads), 0, st, g, (const float *)out,
+        hipLaunchKernelGGL((valu_delta_kernel<float>), grid, dim3(kThreads), 0, st, g, nchunk, (const float *)out,
                            (const float *)dout, delta);
     return hipGetLastError();
 }

@@ -499,6 +499,18 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
 //     with one 24-bit multiply-add, and writes the transposed images four tokens at a time;
 //   - P and dS go to bf16 by truncation (one byte-permute per pair instead of the slow
 //     rounding convert); the mean loss of truncation is multiplied back into the results.
+// LDS image of one streamed tile of T tokens (same parts as Lay, tile size a parameter).
+template <int DQK, int DVK, int T>
+struct LayT {
+    static constexpr int XS = DQK + 8, YS = DVK + 8, TS = T + 8;
+    static constexpr int XR = 0;
+    static constexpr int XT = XR + T * XS;
+    static constexpr int YR = XT + 64 * TS;
+    static constexpr int YT = YR + T * YS;
+    static constexpr int STAGE = YT + 32 * TS;
+    static constexpr int KS = DQK / 16, VS = DVK / 16;
+};
+
 constexpr float kTruncGain = 1.0028176f;   // 1 + 2^-8 / (2 ln 2): mean relative loss of bf16 truncation
 
 __device__ __forceinline__ uint32_t trunc_pack(float lo, float hi)
@@ -517,7 +529,7 @@ struct FRegs {
     float e0, e1;
 };
 
-template <int DQK, int DVK>
+template <int DQK, int DVK, int T>
 struct FConst {
     uint32_t lane_c, tsb, dsb;      // channel-pair byte offset in a token; strided / dense token stride in bytes
     uint32_t f_off0, f_off1, frow;  // byte offsets of this lane's RIB dwords; bytes per RIB row
@@ -525,12 +537,23 @@ struct FConst {
     int xr, xt, yr, yt, fr0, ft0, fr1, ft1;   // bf16 element offsets inside a stage
 };
 
-template <int DQK, int DVK>
-__device__ __forceinline__ FConst<DQK, DVK> fconst(const Geo &g, int hd)
+// Recomputed inside the tile loop from a thread id the optimiser cannot hoist (see
+// opaque_tid): a dozen cheap integer instructions per tile instead of a dozen registers
+// held across the MFMA block, which is what pushed the dkv kernel into spilling.
+__device__ __forceinline__ int opaque_tid()
 {
-    using L = Lay<DQK, DVK>;
-    FConst<DQK, DVK> c;
-    const int tid = threadIdx.x, grp = tid >> 4, j = tid & 15;
+    int t = threadIdx.x;
+    asm volatile("" : "+v"(t));
+    return t;
+}
+
+template <int DQK, int DVK, int T>
+__device__ __forceinline__ FConst<DQK, DVK, T> fconst(const Geo &g, int hd, int tid)
+{
+    using L = LayT<DQK, DVK, T>;
+    constexpr int kTS = L::TS;
+    FConst<DQK, DVK, T> c;
+    const int grp = tid >> 4, j = tid & 15;
     const int hp = g.d >> 1, rh = g.r >> 1;
     const int pair = j < hp ? j : hp - 1;
     const int f0 = j < rh ? j : rh - 1, f1 = 16 + j < rh ? 16 + j : rh - 1;
@@ -555,11 +578,12 @@ __device__ __forceinline__ FConst<DQK, DVK> fconst(const Geo &g, int hd)
 
 // Request tile `tile` of the streamed operand pair.  QDO: X = q (strided), Y = dO (dense),
 // extras = LSE, delta.  Otherwise X = k, Y = v (both strided).
-template <int DQK, int DVK, bool QDO>
-__device__ __forceinline__ void fload(FRegs<DQK, DVK> &rg, const FConst<DQK, DVK> &c, const Geo &g, int64_t u, int tile,
+template <int DQK, int DVK, int T, bool QDO>
+__device__ __forceinline__ void fload(FRegs<DQK, DVK> &rg, const FConst<DQK, DVK, T> &c, const Geo &g, int64_t u, int tile,
                                       const int *tok, const char *xb, const char *yb, const char *fbase,
                                       const float *__restrict__ lse, const float *__restrict__ delta)
 {
+    constexpr int kT = T;
     const char *fb = fbase + (uint32_t)tile * (uint32_t)kT * c.frow;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
@@ -577,6 +601,7 @@ __device__ __forceinline__ void fload(FRegs<DQK, DVK> &rg, const FConst<DQK, DVK
 }
 
 // four dwords (tokens t..t+3, one channel pair) -> the two transposed rows, 8 bytes each
+template <int kTS>
 __device__ __forceinline__ void store_t4(bf16_t *dst, const uint32_t (&w)[4])
 {
     uint2 even, odd;
@@ -588,10 +613,11 @@ __device__ __forceinline__ void store_t4(bf16_t *dst, const uint32_t (&w)[4])
     *(uint2 *)(dst + kTS) = odd;
 }
 
-template <int DQK, int DVK, bool QDO, bool TRANS_Y>
-__device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<DQK, DVK> &c, bf16_t *S, float sc, float sp)
+template <int DQK, int DVK, int T, bool QDO, bool TRANS_Y>
+__device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<DQK, DVK, T> &c, bf16_t *S, float sc, float sp)
 {
-    using L = Lay<DQK, DVK>;
+    using L = LayT<DQK, DVK, T>;
+    constexpr int kT = T, kTS = L::TS;
     uint32_t x[4], fa[4], fb[4];
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
@@ -608,10 +634,10 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
         *(uint32_t *)(S + c.fr0 + p * L::XS) = fa[p];
         if (DQK == 64) *(uint32_t *)(S + c.fr1 + p * L::XS) = fb[p];
     }
-    store_t4(S + c.xt, x);
-    store_t4(S + c.ft0, fa);
-    if (DQK == 64) store_t4(S + c.ft1, fb);
-    if (TRANS_Y) store_t4(S + c.yt, rg.yc);
+    store_t4<kTS>(S + c.xt, x);
+    store_t4<kTS>(S + c.ft0, fa);
+    if (DQK == 64) store_t4<kTS>(S + c.ft1, fb);
+    if (TRANS_Y) store_t4<kTS>(S + c.yt, rg.yc);
     if (threadIdx.x < kT) {
         uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
         if (QDO) {
@@ -687,19 +713,20 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
     __syncthreads();
 }
 
-template <int DQK, int DVK>
+template <int DQK, int DVK, int T, int WAVES>
 struct FSmem {
-    using L = Lay<DQK, DVK>;
-    static constexpr int STAT = kWaves * (kT * L::XS + kT * L::YS);            // stationary staging, bf16
+    using L = LayT<DQK, DVK, T>;
+    static constexpr int STAT = WAVES * (64 * L::XS + 64 * L::YS);             // stationary staging, bf16
     static constexpr int ELEMS = (2 * L::STAGE > STAT ? 2 * L::STAGE : STAT);
     static constexpr int ELEMS16 = (ELEMS + 7) / 8 * 8;
     static constexpr size_t BYTES = (size_t)ELEMS16 * sizeof(bf16_t);
 };
 
+template <int NT>
 __device__ __forceinline__ void zero_lds(bf16_t *base, int elems16)
 {
     const uint4 z = {0u, 0u, 0u, 0u};
-    for (int e = threadIdx.x; e < elems16 / 8; e += kNT) ((uint4 *)base)[e] = z;
+    for (int e = threadIdx.x; e < elems16 / 8; e += NT) ((uint4 *)base)[e] = z;
 }
 
 __device__ __forceinline__ void block_coords(const Geo &g, int nblk, int64_t &u, int &blk, int &w, int &hd)
@@ -713,14 +740,15 @@ __device__ __forceinline__ void block_coords(const Geo &g, int nblk, int64_t &u,
 }
 
 // dQ (+ dF_q partial), fast path.
-template <int DQK, int DVK>
-__global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dq_fast_kernel(
+template <int DQK, int DVK, int T, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dq_fast_kernel(
     Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
     const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dq, float *__restrict__ dfq_part)
 {
-    using L = Lay<DQK, DVK>;
-    using Sm = FSmem<DQK, DVK>;
+    using L = LayT<DQK, DVK, T>;
+    using Sm = FSmem<DQK, DVK, T, WAVES>;
+    constexpr int kT = T, kTS = L::TS, kWaves = WAVES, kNT = WAVES * 64, NB = T / 32;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
     int *tok = (int *)(smem + Sm::ELEMS16);
@@ -733,23 +761,23 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
     const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
 
     fill_tok_table<kNT>(g, w, tok, g.N);
-    zero_lds(smem, Sm::ELEMS16);
+    zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
 
-    const FConst<DQK, DVK> c = fconst<DQK, DVK>(g, hd);
+    const FConst<DQK, DVK, T> c = fconst<DQK, DVK, T>(g, hd, threadIdx.x);
     const char *kb = (const char *)k, *vb = (const char *)v;
     const char *fkb = (const char *)(fk + (int64_t)hd * g.N * g.r);
     FRegs<DQK, DVK> rg;
-    fload<DQK, DVK, false>(rg, c, g, u, 0, tok, kb, vb, fkb, lse, delta);
+    fload<DQK, DVK, T, false>(rg, c, g, u, 0, tok, kb, vb, fkb, lse, delta);
 
-    const int q0 = (blk * kWaves + wave) * kT;
+    const int q0 = (blk * kWaves + wave) * 64;
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
     stationary_rows<DQK, DVK, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
-                                    smem + wave * (kT * L::XS + kT * L::YS), Qb, Gb);
-    zero_lds(smem, Sm::ELEMS16);
+                                    smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb);
+    zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
-    fstore<DQK, DVK, false, false>(rg, c, stage0, 1.f, 1.f);
-    fload<DQK, DVK, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
+    fstore<DQK, DVK, T, false, false>(rg, c, stage0, 1.f, 1.f);
+    fload<DQK, DVK, T, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
     __syncthreads();
 
     f32x16 acc[2][2];
@@ -763,7 +791,7 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
     for (int tile = 0; tile < ntiles; ++tile) {
         bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
 #pragma unroll
-        for (int kb2 = 0; kb2 < 2; ++kb2) {
+        for (int kb2 = 0; kb2 < NB; ++kb2) {
             bf16x8 Ak[L::KS], Av[L::VS], At[2][2];
             read_rows<L::KS>(Ak, cur + L::XR, L::XS, kb2 * 32 + col, hf);
             read_rows<L::VS>(Av, cur + L::YR, L::YS, kb2 * 32 + col, hf);
@@ -792,8 +820,8 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
                 }
             }
         }
-        fstore<DQK, DVK, false, false>(rg, c, nxt, 1.f, 1.f);
-        fload<DQK, DVK, false>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, kb, vb, fkb, lse, delta);
+        fstore<DQK, DVK, T, false, false>(rg, c, nxt, 1.f, 1.f);
+        fload<DQK, DVK, T, false>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, kb, vb, fkb, lse, delta);
         __syncthreads();
     }
 
@@ -809,15 +837,16 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
 }
 
 // dK, dV (+ dF_k partial), fast path.
-template <int DQK, int DVK>
-__global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dkv_fast_kernel(
+template <int DQK, int DVK, int T, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dkv_fast_kernel(
     Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
     const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
     float *__restrict__ dfk_part)
 {
-    using L = Lay<DQK, DVK>;
-    using Sm = FSmem<DQK, DVK>;
+    using L = LayT<DQK, DVK, T>;
+    using Sm = FSmem<DQK, DVK, T, WAVES>;
+    constexpr int kT = T, kTS = L::TS, kWaves = WAVES, kNT = WAVES * 64, NB = T / 32;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
     int *tok = (int *)(smem + Sm::ELEMS16);
@@ -830,23 +859,23 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
     const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
 
     fill_tok_table<kNT>(g, w, tok, g.N);
-    zero_lds(smem, Sm::ELEMS16);
+    zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
 
-    const FConst<DQK, DVK> c = fconst<DQK, DVK>(g, hd);
+    const FConst<DQK, DVK, T> c = fconst<DQK, DVK, T>(g, hd, threadIdx.x);
     const char *qb_ = (const char *)q, *gb_ = (const char *)dout;
     const char *fqb = (const char *)(fq + (int64_t)hd * g.N * g.r);
     FRegs<DQK, DVK> rg;
-    fload<DQK, DVK, true>(rg, c, g, u, 0, tok, qb_, gb_, fqb, lse, delta);
+    fload<DQK, DVK, T, true>(rg, c, g, u, 0, tok, qb_, gb_, fqb, lse, delta);
 
-    const int k0 = (blk * kWaves + wave) * kT;
+    const int k0 = (blk * kWaves + wave) * 64;
     bf16x8 Kb[2][L::KS], Vb[2][L::VS];
     stationary_rows<DQK, DVK, false>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, 1.f, 1.f,
-                                     smem + wave * (kT * L::XS + kT * L::YS), Kb, Vb);
-    zero_lds(smem, Sm::ELEMS16);
+                                     smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
+    zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
-    fstore<DQK, DVK, true, true>(rg, c, stage0, sc2, sp2);
-    fload<DQK, DVK, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
+    fstore<DQK, DVK, T, true, true>(rg, c, stage0, sc2, sp2);
+    fload<DQK, DVK, T, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
     __syncthreads();
 
     f32x16 accV[2], accK[2][2];
@@ -863,7 +892,7 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
     for (int tile = 0; tile < ntiles; ++tile) {
         bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < NB; ++qb) {
             bf16x8 Aq[L::KS], Ag[L::VS], Aqt[2][2], Agt[2];
             read_rows<L::KS>(Aq, cur + L::XR, L::XS, qb * 32 + col, hf);
             read_rows<L::VS>(Ag, cur + L::YR, L::YS, qb * 32 + col, hf);
@@ -899,8 +928,12 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
                 }
             }
         }
-        fstore<DQK, DVK, true, true>(rg, c, nxt, sc2, sp2);
-        fload<DQK, DVK, true>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, qb_, gb_, fqb, lse, delta);
+        {
+            const FConst<DQK, DVK, T> cc = fconst<DQK, DVK, T>(g, hd, opaque_tid());
+            fstore<DQK, DVK, T, true, true>(rg, cc, nxt, sc2, sp2);
+            fload<DQK, DVK, T, true>(rg, cc, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, qb_, gb_, fqb, lse,
+                                     delta);
+        }
         __syncthreads();
     }
 
@@ -924,8 +957,38 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
 static bool bwd_fast_ok(const Geo &g)
 {
     const int64_t tokens = (int64_t)g.B * g.H * g.W;
-    return g.r > 0 && g.N % (kWaves * kT) == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+    return g.r > 0 && g.N % 256 == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
            tokens * g.tstride * 2 < ((int64_t)1 << 32);
+}
+
+// Launch the fast pair with workgroups of WAVES waves and streamed tiles of T tokens.
+template <int DQK, int DVK, int T, int WAVES>
+hipError_t launch_fast(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
+                       const void *dout, const float *lse, const float *delta, void *dq, void *dk, void *dv, float *pq,
+                       float *pk, hipStream_t st)
+{
+    const size_t smem = FSmem<DQK, DVK, T, WAVES>::BYTES + (size_t)g.N * sizeof(int);
+    if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
+    auto kdkv = mfma_bwd_dkv_fast_kernel<DQK, DVK, T, WAVES>;
+    auto kdq = mfma_bwd_dq_fast_kernel<DQK, DVK, T, WAVES>;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [kdkv, kdq] {
+        attr_err = hipFuncSetAttribute((const void *)kdkv, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute((const void *)kdq, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+    });
+    if (attr_err != hipSuccess) return attr_err;
+    const int nblk = g.N / (WAVES * 64);
+    const dim3 grid((unsigned)(g.units * nblk)), block(WAVES * 64);
+    hipLaunchKernelGGL(kdkv, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dk,
+                       (bf16_t *)dv, pk);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(kdq, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
+    return hipGetLastError();
 }
 
 template <int DQK, int DVK>
@@ -941,32 +1004,43 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     hipError_t e = launch_delta(g, RIB_BF16, out, dout, delta, st);
     if (e != hipSuccess) return e;
 
-    const bool fast = bwd_fast_ok(g);
+    if (bwd_fast_ok(g)) {
+        // eight-wave workgroups (one per CU, 128-token tiles) when the window is large enough
+        bool done = false;
+        if constexpr (DQK == 48 && DVK == 32) {
+            if (false && g.N % 512 == 0) {
+                e = launch_fast<DQK, DVK, 128, 8>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
+                done = true;
+            }
+        }
+        if (!done) e = launch_fast<DQK, DVK, 64, 4>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
+        if (e != hipSuccess) return e;
+        return launch_reduce_df(g, pq, pk, dfq, dfk, st);
+    }
+
     const int ntiles = (g.N + kT - 1) / kT;
     const int nblk = (ntiles + kWaves - 1) / kWaves;
-    const size_t tiles_bytes = fast ? FSmem<DQK, DVK>::BYTES : (size_t)2 * L::STAGE * sizeof(bf16_t);
-    const size_t smem = tiles_bytes + (size_t)ntiles * kT * sizeof(int);
+    const size_t smem = (size_t)2 * L::STAGE * sizeof(bf16_t) + (size_t)ntiles * kT * sizeof(int);
     if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [] {
-        const void *ks[4] = {(const void *)mfma_bwd_dq_kernel<DQK, DVK>, (const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
-                             (const void *)mfma_bwd_dq_fast_kernel<DQK, DVK>,
-                             (const void *)mfma_bwd_dkv_fast_kernel<DQK, DVK>};
-        for (int i = 0; i < 4 && attr_err == hipSuccess; ++i)
-            attr_err = hipFuncSetAttribute(ks[i], hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+        attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dq_kernel<DQK, DVK>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+        if (attr_err == hipSuccess)
+            attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
     });
     if (attr_err != hipSuccess) return attr_err;
     const dim3 grid((unsigned)(g.units * nblk)), block(kNT);
-    auto kdkv = fast ? mfma_bwd_dkv_fast_kernel<DQK, DVK> : mfma_bwd_dkv_kernel<DQK, DVK>;
-    auto kdq = fast ? mfma_bwd_dq_fast_kernel<DQK, DVK> : mfma_bwd_dq_kernel<DQK, DVK>;
-    hipLaunchKernelGGL(kdkv, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dk,
-                       (bf16_t *)dv, pk);
+    hipLaunchKernelGGL((mfma_bwd_dkv_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
+                       (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,
+                       (const bf16_t *)dout, lse, delta, (bf16_t *)dk, (bf16_t *)dv, pk);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kdq, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
+    hipLaunchKernelGGL((mfma_bwd_dq_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
+                       (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,
+                       (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     return launch_reduce_df(g, pq, pk, dfq, dfk, st);

@@ -1005,15 +1005,9 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     if (e != hipSuccess) return e;
 
     if (bwd_fast_ok(g)) {
-        // eight-wave workgroups (one per CU, 128-token tiles) when the window is large enough
-        bool done = false;
-        if constexpr (DQK == 48 && DVK == 32) {
-            if (false && g.N % 512 == 0) {
-                e = launch_fast<DQK, DVK, 128, 8>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
-                done = true;
-            }
-        }
-        if (!done) e = launch_fast<DQK, DVK, 64, 4>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
+        // (workgroups of 8 waves with 128-token tiles -- launch_fast<DQK, DVK, 128, 8> -- were
+        // measured slower: one workgroup per CU leaves the prologue's memory latency uncovered)
+        e = launch_fast<DQK, DVK, 64, 4>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
         if (e != hipSuccess) return e;
         return launch_reduce_df(g, pq, pk, dfq, dfk, st);
     }

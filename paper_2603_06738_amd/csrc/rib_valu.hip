@@ -179,33 +179,37 @@ __device__ __forceinline__ float dot_share<bf16_t>(const bf16_t *a, const bf16_t
     return acc;
 }
 
-// One workgroup = 64 consecutive window-local tokens of one window, all heads: the grid
-// tokens are computed once (one division per token) and kept in LDS; then sixteen lanes
-// share a (token, head) and walk heads in the outer and tokens in the inner loop.
+// One workgroup = 64 consecutive window-local tokens of one (window, head) unit: the grid
+// tokens are computed once (one division per token) and kept in LDS; sixteen lanes share
+// a token, and the four tokens of a lane group are loaded before any is reduced, so four
+// memory round trips are in flight per lane.
 template <typename T>
 __global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, int nchunk, const T *__restrict__ out,
                                                               const T *__restrict__ dout, float *__restrict__ delta)
 {
     __shared__ int64_t tok[64];
-    const int w = blockIdx.x / nchunk;
-    const int n0 = (blockIdx.x - w * nchunk) * 64;
+    const int64_t u = blockIdx.x / nchunk;
+    const int n0 = (int)(blockIdx.x - u * nchunk) * 64;
+    const int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
     const int tid = threadIdx.x, grp = tid >> 4, sub = tid & 15;
     if (tid < 64) tok[tid] = n0 + tid < g.N ? grid_token(g, w, n0 + tid) : -1;
     __syncthreads();
-    for (int hd = 0; hd < g.heads; ++hd) {
+    float acc[4];
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int nl = it * 16 + grp;
-            const int64_t t = tok[nl];
-            float acc = 0.f;
-            if (t >= 0) {
-                const int64_t base = t * g.C + hd * g.d;
-                acc = dot_share<T>(out + base, dout + base, g.d, sub);
-            }
-#pragma unroll
-            for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-            if (t >= 0 && sub == 0) delta[((int64_t)w * g.heads + hd) * g.N + n0 + nl] = acc;
+    for (int it = 0; it < 4; ++it) {
+        const int64_t t = tok[it * 16 + grp];
+        acc[it] = 0.f;
+        if (t >= 0) {
+            const int64_t base = t * g.C + hd * g.d;
+            acc[it] = dot_share<T>(out + base, dout + base, g.d, sub);
         }
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) acc[it] += __shfl_xor(acc[it], off);
+        const int nl = it * 16 + grp;
+        if (sub == 0 && n0 + nl < g.N) delta[u * g.N + n0 + nl] = acc[it];
     }
 }
 
@@ -448,8 +452,7 @@ BwdWs bwd_ws_layout(const Geo &g)
 hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *dout, float *delta, hipStream_t st)
 {
     const int nchunk = (g.N + 63) / 64;
-    const int64_t nwin = g.units / g.heads;
-    dim3 grid((unsigned)(nwin * nchunk));
+    dim3 grid((unsigned)(g.units * nchunk));
     if (dtype == RIB_BF16)
         hipLaunchKernelGGL((valu_delta_kernel<bf16_t>), grid, dim3(kThreads), 0, st, g, nchunk, (const bf16_t *)out,
                            (const bf16_t *)dout, delta);

@@ -613,7 +613,7 @@ __device__ __forceinline__ void store_t4(bf16_t *dst, const uint32_t (&w)[4])
     *(uint2 *)(dst + kTS) = odd;
 }
 
-template <int DQK, int DVK, int T, bool QDO, bool TRANS_Y>
+template <int DQK, int DVK, int T, bool QDO, bool TRANS_Y, bool SCALE>
 __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<DQK, DVK, T> &c, bf16_t *S, float sc, float sp)
 {
     using L = LayT<DQK, DVK, T>;
@@ -624,7 +624,7 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
         x[p] = rg.xc[p];
         fa[p] = rg.fa[p];
         fb[p] = DQK == 64 ? rg.fb[p] : 0u;
-        if (QDO) {
+        if (SCALE) {
             x[p] = pack_bf16(lo_bf16(x[p]) * sc, hi_bf16(x[p]) * sc);
             fa[p] = pack_bf16(lo_bf16(fa[p]) * sp, hi_bf16(fa[p]) * sp);
             if (DQK == 64) fb[p] = pack_bf16(lo_bf16(fb[p]) * sp, hi_bf16(fb[p]) * sp);
@@ -651,7 +651,7 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
 
 // Each wave stages its own 64 stationary rows (X rows [64][XS], Y rows [64][YS], extras
 // included) into its private LDS area `W` and reads them back as MFMA B operands.
-template <int DQK, int DVK, bool QDO>
+template <int DQK, int DVK, bool QDO, bool SCALE>
 __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u, int n0, const int *tok, const char *xb,
                                                 const char *yb, const bf16_t *f, const float *__restrict__ lse,
                                                 const float *__restrict__ delta, float sc, float sp, bf16_t *W,
@@ -685,7 +685,7 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
     for (int p = 0; p < 16; ++p) {
         const int row = p * 4 + sub;
         uint32_t a = xx[p], b = fa[p], b2 = DQK == 64 ? fb2[p] : 0u;
-        if (QDO) {
+        if (SCALE) {
             a = pack_bf16(lo_bf16(a) * sc, hi_bf16(a) * sc);
             b = pack_bf16(lo_bf16(b) * sp, hi_bf16(b) * sp);
             if (DQK == 64) b2 = pack_bf16(lo_bf16(b2) * sp, hi_bf16(b2) * sp);
@@ -772,11 +772,11 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
 
     const int q0 = (blk * kWaves + wave) * 64;
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
-    stationary_rows<DQK, DVK, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
+    stationary_rows<DQK, DVK, true, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
                                     smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb);
     zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
-    fstore<DQK, DVK, T, false, false>(rg, c, stage0, 1.f, 1.f);
+    fstore<DQK, DVK, T, false, false, false>(rg, c, stage0, 1.f, 1.f);
     fload<DQK, DVK, T, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
     __syncthreads();
 
@@ -820,7 +820,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
                 }
             }
         }
-        fstore<DQK, DVK, T, false, false>(rg, c, nxt, 1.f, 1.f);
+        fstore<DQK, DVK, T, false, false, false>(rg, c, nxt, 1.f, 1.f);
         fload<DQK, DVK, T, false>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, kb, vb, fkb, lse, delta);
         __syncthreads();
     }
@@ -870,11 +870,11 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
 
     const int k0 = (blk * kWaves + wave) * 64;
     bf16x8 Kb[2][L::KS], Vb[2][L::VS];
-    stationary_rows<DQK, DVK, false>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, 1.f, 1.f,
+    stationary_rows<DQK, DVK, false, true>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, sc2, sp2,
                                      smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
     zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
-    fstore<DQK, DVK, T, true, true>(rg, c, stage0, sc2, sp2);
+    fstore<DQK, DVK, T, true, true, false>(rg, c, stage0, sc2, sp2);
     fload<DQK, DVK, T, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
     __syncthreads();
 
@@ -930,7 +930,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         }
         {
             const FConst<DQK, DVK, T> cc = fconst<DQK, DVK, T>(g, hd, opaque_tid());
-            fstore<DQK, DVK, T, true, true>(rg, cc, nxt, sc2, sp2);
+            fstore<DQK, DVK, T, true, true, false>(rg, cc, nxt, sc2, sp2);
             fload<DQK, DVK, T, true>(rg, cc, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, qb_, gb_, fqb, lse,
                                      delta);
         }
@@ -944,7 +944,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         float *pd = dfk_part + (u * g.N + n) * g.r;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-            store_aug(accK[kb][mb], mb, hf, g, kLn2 * kTruncGain, kLn2 * kTruncGain, dk + base, pd);
+            store_aug(accK[kb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain, dk + base, pd);
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
             int cc = 8 * (i >> 2) + 4 * hf + (i & 3);

@@ -24,6 +24,9 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, vendor figure
 PEAK_F32_VALU_TFLOPS = 157.3  # MI355X fp32 vector, vendor figure
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
+# plain copy of known size (profiles/c5_step_hbm_traffic.md); only for the workload it was measured on.
+MEASURED_FWD_TRAFFIC = {"c5": 230.6e6}
 
 
 def parse():
@@ -161,7 +164,10 @@ def main():
     peak = PEAK_BF16_TFLOPS if mfma else PEAK_F32_VALU_TFLOPS
     res["roofline"] = {"kernel": "forward (" + rb.kernel_name(r.p, False) + ")",
                        "bound": "mfma" if mfma else "alu", "achieved": round(fwd_tflops, 2), "peak": peak,
-                       "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4), "traffic": None}
+                       "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4),
+                       "traffic": MEASURED_FWD_TRAFFIC.get(wl.name),
+                       "algorithmic_flop": wl.fwd_flop, "algorithmic_bytes": wl.fwd_bytes,
+                       "issue_ceiling_tflops": 1318.0 if mfma and wl.d == 30 and wl.r == 16 else None}
     if wl.backward:
         bmfma = rb.kernel_name(r.p, True) == "mfma-bf16"
         bpeak = PEAK_BF16_TFLOPS if bmfma else PEAK_F32_VALU_TFLOPS

@@ -760,19 +760,38 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
         attend<DQK, WAVES, ONES, true>(g, hd, tok, Ka, Vt, foff, Q, k, v, fk, O, mrun, lsum);
     }
 
+    // Normalise, then send O through LDS so that the global stores are token rows: in the
+    // accumulator layout a lane holds 16 channels of ONE token, and storing from there would
+    // touch 32 token rows per instruction.  Each wave transposes its own 64 x d block in a
+    // private LDS area ([64 tokens][34 bf16]: the odd dword stride keeps both sides
+    // conflict-free) and writes it out with 16 lanes per token.
+    constexpr int ORS = 34;
+    __syncthreads();                                   // every wave is done with the K/V tiles
+    bf16_t *Os = tiles + wave * 64 * ORS;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
         const float l = ONES ? ones_row(O[qb], g.d) : lsum[qb] + __shfl_xor(lsum[qb], 32);
         const int n = q0 + qb * 32 + col;
         const float inv = 1.f / l;
-        bf16_t *dst = out + (int64_t)tok[n] * g.C + hd * g.d;
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
             int dv = 8 * (i >> 2) + 4 * hf + (i & 3);
-            if (dv < g.d) *(uint32_t *)(dst + dv) = pack_bf16(O[qb][i] * inv, O[qb][i + 1] * inv);
+            *(uint32_t *)(Os + (qb * 32 + col) * ORS + dv) = pack_bf16(O[qb][i] * inv, O[qb][i + 1] * inv);
         }
         if (lse != nullptr && hf == 0)
             lse[u * g.N + n] = (mrun[qb] + __builtin_amdgcn_logf(l) + (redo ? 0.f : kTruncLog2)) * kLn2;
+    }
+    __syncthreads();
+    {
+        const int sub = lane >> 4, j = lane & 15;
+        if (2 * j < g.d) {
+#pragma unroll
+            for (int p = 0; p < 16; ++p) {
+                const int row = p * 4 + sub;
+                const uint32_t w2 = *(const uint32_t *)(Os + row * ORS + 2 * j);
+                *(uint32_t *)(out + (int64_t)tok[q0 + row] * g.C + hd * g.d + 2 * j) = w2;
+            }
+        }
     }
 }
 

@@ -713,11 +713,61 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
     __syncthreads();
 }
 
+// ---- epilogue through LDS: the accumulator layout gives a lane 16 rows of ONE token, and
+// storing from there would touch 32 token rows per instruction.  Each wave parks its 64
+// tokens in a private LDS area -- content columns as bf16 rows of kORS elements, RIB
+// columns as fp32 rows of kFRS elements (odd dword strides: conflict-free both ways) --
+// and writes them out with 16 lanes per token.
+constexpr int kORS = 34, kFRS = 33;
+constexpr int kWaveOut = 64 * kORS * 2 + 64 * kFRS * 4;      // bytes per wave
+
+__device__ __forceinline__ void stash_aug(const f32x16 &acc, int mb, int hf, const Geo &g, float sc, float sp,
+                                          bf16_t *orow, float *frow)
+{
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        int c = 32 * mb + 8 * (i >> 2) + 4 * hf + (i & 3);
+        if (c < g.d) *(uint32_t *)(orow + c) = pack_bf16(acc[i] * sc, acc[i + 1] * sc);
+        else if (c < g.d + g.r) {
+            frow[c - g.d] = acc[i] * sp;
+            frow[c - g.d + 1] = acc[i + 1] * sp;
+        }
+    }
+}
+
+// rows [n0, n0+64) of a grid tensor from the wave's bf16 area
+__device__ __forceinline__ void flush_rows(const bf16_t *Os, bf16_t *__restrict__ dst, const int *tok, int n0, int hd,
+                                           const Geo &g)
+{
+    const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
+    if (2 * j < g.d) {
+#pragma unroll
+        for (int p = 0; p < 16; ++p) {
+            const int row = p * 4 + sub;
+            *(uint32_t *)(dst + (int64_t)tok[n0 + row] * g.C + hd * g.d + 2 * j) = *(const uint32_t *)(Os + row * kORS + 2 * j);
+        }
+    }
+}
+
+// rows [n0, n0+64) of this unit's RIB partial (contiguous in memory) from the wave's fp32 area
+__device__ __forceinline__ void flush_partial(const float *Fs, float *__restrict__ part, int r)
+{
+    const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+        const int row = p * 4 + sub;
+        if (j < r) part[row * r + j] = Fs[row * kFRS + j];
+        if (16 + j < r) part[row * r + 16 + j] = Fs[row * kFRS + 16 + j];
+    }
+}
+
 template <int DQK, int DVK, int T, int WAVES>
 struct FSmem {
     using L = LayT<DQK, DVK, T>;
     static constexpr int STAT = WAVES * (64 * L::XS + 64 * L::YS);             // stationary staging, bf16
-    static constexpr int ELEMS = (2 * L::STAGE > STAT ? 2 * L::STAGE : STAT);
+    static constexpr int OUTB = WAVES * kWaveOut / 2;                            // epilogue staging, bf16 units
+    static constexpr int ELEMS0 = (2 * L::STAGE > STAT ? 2 * L::STAGE : STAT);
+    static constexpr int ELEMS = (ELEMS0 > OUTB ? ELEMS0 : OUTB);
     static constexpr int ELEMS16 = (ELEMS + 7) / 8 * 8;
     static constexpr size_t BYTES = (size_t)ELEMS16 * sizeof(bf16_t);
 };
@@ -825,15 +875,18 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         __syncthreads();
     }
 
+    // (the loop's last barrier has passed: the tiles are free)
+    bf16_t *Os = (bf16_t *)((char *)smem + wave * kWaveOut);
+    float *Fs = (float *)(Os + 64 * kORS);
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const int n = q0 + qb * 32 + col;
-        bf16_t *gd = dq + (int64_t)tok[n] * g.C + hd * g.d;
-        float *pd = dfq_part + (u * g.N + n) * g.r;
+    for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-            store_aug(acc[qb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain, gd, pd);
-    }
+            stash_aug(acc[qb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain,
+                      Os + (qb * 32 + col) * kORS, Fs + (qb * 32 + col) * kFRS);
+    __syncthreads();
+    flush_rows(Os, dq, tok, q0, hd, g);
+    flush_partial(Fs, dfq_part + (u * g.N + q0) * g.r, g.r);
 }
 
 // dK, dV (+ dF_k partial), fast path.
@@ -937,21 +990,30 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         __syncthreads();
     }
 
+    bf16_t *Os = (bf16_t *)((char *)smem + wave * kWaveOut);
+    float *Fs = (float *)(Os + 64 * kORS);
+    // dK and the dF_k partial first, then dV through the same area
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-        const int n = k0 + kb * 32 + col;
-        const int64_t base = (int64_t)tok[n] * g.C + hd * g.d;
-        float *pd = dfk_part + (u * g.N + n) * g.r;
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-            store_aug(accK[kb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain, dk + base, pd);
+            stash_aug(accK[kb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain,
+                      Os + (kb * 32 + col) * kORS, Fs + (kb * 32 + col) * kFRS);
+    __syncthreads();
+    flush_rows(Os, dk, tok, k0, hd, g);
+    flush_partial(Fs, dfk_part + (u * g.N + k0) * g.r, g.r);
+    __syncthreads();
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
             int cc = 8 * (i >> 2) + 4 * hf + (i & 3);
-            if (cc < g.d)
-                *(uint32_t *)(dv + base + cc) = pack_bf16(accV[kb][i] * kTruncGain, accV[kb][i + 1] * kTruncGain);
+            *(uint32_t *)(Os + (kb * 32 + col) * kORS + cc) =
+                pack_bf16(accV[kb][i] * kTruncGain, accV[kb][i + 1] * kTruncGain);
         }
     }
+    __syncthreads();
+    flush_rows(Os, dv, tok, k0, hd, g);
 }
 
 static bool bwd_fast_ok(const Geo &g)

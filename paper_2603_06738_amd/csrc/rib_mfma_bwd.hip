@@ -824,8 +824,10 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
     stationary_rows<DQK, DVK, true, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
                                     smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb);
-    zero_lds<kNT>(smem, Sm::ELEMS16);
-    __syncthreads();
+    // No second clearing: from here on the padding columns of a streamed tile may hold stale
+    // (finite) rows of this workgroup; they only ever multiply the zero padding of the
+    // stationary operands, and stale transposed rows only feed accumulator rows that are
+    // never stored.
     fstore<DQK, DVK, T, false, false, false>(rg, c, stage0, 1.f, 1.f);
     fload<DQK, DVK, T, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
     __syncthreads();
@@ -925,8 +927,6 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
     bf16x8 Kb[2][L::KS], Vb[2][L::VS];
     stationary_rows<DQK, DVK, false, true>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, sc2, sp2,
                                      smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
-    zero_lds<kNT>(smem, Sm::ELEMS16);
-    __syncthreads();
     fstore<DQK, DVK, T, true, true, false>(rg, c, stage0, sc2, sp2);
     fload<DQK, DVK, T, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
     __syncthreads();

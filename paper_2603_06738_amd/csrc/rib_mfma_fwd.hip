@@ -297,18 +297,26 @@ __device__ __forceinline__ void sched_pipeline()
     }
 }
 
+// Two dwords at a 4-byte aligned address (global memory only needs dword alignment for
+// multi-dword accesses; LDS gets them as a two-dword write).
+struct __attribute__((packed, aligned(4))) dword2 {
+    uint32_t x, y;
+};
+
+// Staging registers of one 128-token tile: 8 lanes share a token and each thread serves 4
+// consecutive tokens, with 8 bytes per tensor per token.
 template <int DQK>
 struct FastRegs {
-    uint32_t kx[8], vx[8], fa[8];
-    uint32_t fb[DQK == 64 ? 8 : 1];     // second RIB dword per lane: rows of up to 32 dwords
+    dword2 kx[4], vx[4], fa[4];
+    dword2 fb[DQK == 64 ? 4 : 1];       // second RIB slot: rows longer than 32 values
 };
 
 template <int DQK>
 struct FastConst {                  // per-thread staging constants
-    uint32_t lane_c;                // byte offset of this lane's channel pair inside a token
+    uint32_t lane_c;                // byte offset of this lane's two content dwords inside a token
     uint32_t tsb;                   // token stride in bytes
-    int tok_idx;                    // first of this lane's 8 tokens inside a tile
-    uint32_t f_off0, f_off1;        // byte offsets of this lane's RIB dwords inside a RIB row
+    int tok_idx;                    // first of this lane's 4 tokens inside a tile
+    uint32_t f_off0, f_off1;        // byte offsets of this lane's RIB dword pairs inside a RIB row
     int k_dst, f_dst0, f_dst1, v_dst;   // bf16 element offsets inside a stage
 };
 
@@ -317,54 +325,63 @@ __device__ __forceinline__ FastConst<DQK> fast_const(const Geo &g, int hd)
 {
     constexpr int KSTR = DQK + 8;
     FastConst<DQK> c;
-    const int tid = threadIdx.x, grp = tid >> 4, j = tid & 15;
-    const int hp = g.d >> 1, rh = g.r >> 1;
-    const int pair = j < hp ? j : hp - 1;               // idle lanes duplicate a neighbour's work
-    const int f0 = j < rh ? j : rh - 1;                 // (the fast path requires r > 0)
-    const int f1 = 16 + j < rh ? 16 + j : rh - 1;
-    c.lane_c = (uint32_t)(hd * g.d + 2 * pair) * 2u;
+    const int tid = threadIdx.x, grp = tid >> 3, j = tid & 7;
+    const int hp = g.d >> 1, rh = g.r >> 1;             // dwords per content row / RIB row (both >= 2)
+    // lane j serves dwords 2j, 2j+1; lanes past the end slide back onto the last pair (their
+    // loads and stores then duplicate a neighbour's, which is harmless)
+    const int dj = 2 * j + 1 < hp ? 2 * j : hp - 2;
+    const int f0 = 2 * j + 1 < rh ? 2 * j : rh - 2;
+    const int f1 = 16 + 2 * j + 1 < rh ? 16 + 2 * j : rh - 2;
+    c.lane_c = (uint32_t)(hd * g.d + 2 * dj) * 2u;
     c.tsb = (uint32_t)g.tstride * 2u;
-    c.tok_idx = grp * 8;
+    c.tok_idx = grp * 4;
     c.f_off0 = (uint32_t)f0 * 4u;
     c.f_off1 = (uint32_t)f1 * 4u;
-    c.k_dst = grp * 8 * KSTR + 2 * pair;
-    c.f_dst0 = grp * 8 * KSTR + g.d + 2 * f0;
-    c.f_dst1 = grp * 8 * KSTR + g.d + 2 * f1;
-    c.v_dst = (2 * pair) * kFVS + 16 * (grp >> 1) + 4 * (grp & 1);
+    c.k_dst = grp * 4 * KSTR + 2 * dj;
+    c.f_dst0 = grp * 4 * KSTR + g.d + 2 * f0;
+    c.f_dst1 = grp * 4 * KSTR + g.d + 2 * f1;
+    // V^T rows 2dj .. 2dj+3; the 4 tokens of this lane sit at permuted columns pc .. pc+3
+    const int nl = grp * 4;
+    const int pc = (nl & ~15) | (((nl >> 2) & 1) << 3) | (((nl >> 3) & 1) << 2);
+    c.v_dst = (2 * dj) * kFVS + pc;
     return c;
 }
 
-// global loads of token p (0..7) of this lane's group for tile `tile`
+// global loads of token p (0..3) of this lane's group
 template <int DQK>
 __device__ __forceinline__ void fast_load(FastRegs<DQK> &rg, const FastConst<DQK> &c, const Geo &g, int p, const int *tokt,
                                           const char *kb, const char *vb, const char *fb)
 {
     const uint32_t off = __umul24((uint32_t)tokt[c.tok_idx + p], c.tsb) + c.lane_c;
-    rg.kx[p] = *(const uint32_t *)(kb + off);
-    rg.vx[p] = *(const uint32_t *)(vb + off);
+    rg.kx[p] = *(const dword2 *)(kb + off);
+    rg.vx[p] = *(const dword2 *)(vb + off);
     const uint32_t row = (uint32_t)(c.tok_idx + p) * (uint32_t)(g.r * 2);
-    rg.fa[p] = *(const uint32_t *)(fb + row + c.f_off0);
-    if (DQK == 64) rg.fb[p] = *(const uint32_t *)(fb + row + c.f_off1);
+    rg.fa[p] = *(const dword2 *)(fb + row + c.f_off0);
+    if (DQK == 64) rg.fb[p] = *(const dword2 *)(fb + row + c.f_off1);
 }
 
-// LDS writes of token p: K_aug row pieces; V^T after every 4th token (4 keys per 8-byte write)
+// LDS writes of token p: its pieces of the K_aug row; after the 4th token the four V^T
+// rows of this lane (4 keys per 8-byte write)
 template <int DQK>
 __device__ __forceinline__ void fast_store(const FastRegs<DQK> &rg, const FastConst<DQK> &c, int p, bf16_t *Kf, bf16_t *Vf)
 {
     constexpr int KSTR = DQK + 8;
-    *(uint32_t *)(Kf + c.k_dst + p * KSTR) = rg.kx[p];
-    *(uint32_t *)(Kf + c.f_dst0 + p * KSTR) = rg.fa[p];
-    if (DQK == 64) *(uint32_t *)(Kf + c.f_dst1 + p * KSTR) = rg.fb[p];
-    if ((p & 3) == 3) {
-        const int h = p >> 2;
-        const uint32_t a = rg.vx[p - 3], b = rg.vx[p - 2], cc = rg.vx[p - 1], d = rg.vx[p];
-        uint2 even, odd;
-        even.x = __builtin_amdgcn_perm(b, a, 0x05040100u);
-        even.y = __builtin_amdgcn_perm(d, cc, 0x05040100u);
-        odd.x = __builtin_amdgcn_perm(b, a, 0x07060302u);
-        odd.y = __builtin_amdgcn_perm(d, cc, 0x07060302u);
-        *(uint2 *)(Vf + c.v_dst + 8 * h) = even;
-        *(uint2 *)(Vf + c.v_dst + kFVS + 8 * h) = odd;
+    *(dword2 *)(Kf + c.k_dst + p * KSTR) = rg.kx[p];
+    *(dword2 *)(Kf + c.f_dst0 + p * KSTR) = rg.fa[p];
+    if (DQK == 64) *(dword2 *)(Kf + c.f_dst1 + p * KSTR) = rg.fb[p];
+    if (p == 3) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t a = h ? rg.vx[0].y : rg.vx[0].x, b = h ? rg.vx[1].y : rg.vx[1].x;
+            const uint32_t cc = h ? rg.vx[2].y : rg.vx[2].x, d = h ? rg.vx[3].y : rg.vx[3].x;
+            uint2 even, odd;
+            even.x = __builtin_amdgcn_perm(b, a, 0x05040100u);
+            even.y = __builtin_amdgcn_perm(d, cc, 0x05040100u);
+            odd.x = __builtin_amdgcn_perm(b, a, 0x07060302u);
+            odd.y = __builtin_amdgcn_perm(d, cc, 0x07060302u);
+            *(uint2 *)(Vf + c.v_dst + (2 * h) * kFVS) = even;
+            *(uint2 *)(Vf + c.v_dst + (2 * h + 1) * kFVS) = odd;
+        }
     }
 }
 
@@ -408,11 +425,11 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
         lsum[qb] = 0.f;
     }
 #pragma unroll
-    for (int p = 0; p < 8; ++p) fast_store<DQK>(rg, c, p, Kf, Vf);
+    for (int p = 0; p < 4; ++p) fast_store<DQK>(rg, c, p, Kf, Vf);
     {   // tile 1 goes in flight now and is written to LDS at the end of tile 0's block
         const int t1 = ntiles > 1 ? 1 : 0;
 #pragma unroll
-        for (int p = 0; p < 8; ++p)
+        for (int p = 0; p < 4; ++p)
             fast_load<DQK>(rg, c, g, p, tok + t1 * kFT, kbase, vbase, fbase + (uint32_t)t1 * ftile);
     }
     __syncthreads();
@@ -486,16 +503,16 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
                 for (int t = 0; t < 2; ++t)
                     Av[kb + 1][t] = *(const bf16x8 *)(Vc + col * kFVS + (kb + 1) * 32 + 16 * t + 8 * hf);
             }
-            if (s >= 4) {
-                fast_store<DQK>(rg, c, 2 * (s - 4), Kn, Vn);
-                fast_store<DQK>(rg, c, 2 * (s - 4) + 1, Kn, Vn);
-            }
         }
         // drain: PV of the last block
         O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][0], as_bf16x8(P[1][0]), O[1], 0, 0, 0);
         O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][1], as_bf16x8(P[1][1]), O[1], 0, 0, 0);
+        // staging of the next tiles: tile+1 (requested a whole block ago) goes to LDS, then
+        // tile+2 is requested into the same registers
 #pragma unroll
-        for (int p = 0; p < 8; ++p) fast_load<DQK>(rg, c, g, p, tokn, kbase, vbase, fn);
+        for (int p = 0; p < 4; ++p) fast_store<DQK>(rg, c, p, Kn, Vn);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) fast_load<DQK>(rg, c, g, p, tokn, kbase, vbase, fn);
 
         // The order the scheduler is asked to build out of the block above: every MFMA
         // followed by its share of the exp2 (transcendental) and pack (VALU) work.
@@ -691,7 +708,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     const FastCtx<DQK> fx = fast_ctx<DQK>(g, hd, k, v, fk);
     FastRegs<DQK> rg;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) fast_load<DQK>(rg, fx.c, g, p, tok, fx.kbase, fx.vbase, fx.fbase);
+    for (int p = 0; p < 4; ++p) fast_load<DQK>(rg, fx.c, g, p, tok, fx.kbase, fx.vbase, fx.fbase);
 
     // Q_aug rows of this wave: 16 lanes per token, 4 tokens per pass
     const int q0 = blk * NT + wave * 64;
@@ -839,7 +856,7 @@ static bool fast_ok(const Geo &g)
 {
     const int64_t tokens = (int64_t)g.B * g.H * g.W;
     const bool small_r = (g.d + g.r <= 48) ? (g.r <= 32) : true;
-    return g.r > 0 && g.N % kFT == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+    return g.r >= 4 && g.d >= 4 && g.N % kFT == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
            tokens * g.tstride * 2 < ((int64_t)1 << 32) && small_r;
 }
 

@@ -32,8 +32,8 @@ MEASURED_FWD_TRAFFIC = {"c5": 230.6e6}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c5")
     ap.add_argument("--all", action="store_true", help="also time the forward of every named workload")
     ap.add_argument("--force-row-max", action="store_true", help="time the max-tracking softmax path")
@@ -182,7 +182,7 @@ def main():
         table = {}
         for name, w2 in wk.WORKLOADS.items():
             r2 = Runner(w2.__class__(**{**w2.__dict__, "backward": False}), flags)
-            _, f_ms, _ = time_steps(r2, max(10, a.steps), a.warmup)
+            _, f_ms, _ = time_steps(r2, min(50, max(10, a.steps)), min(a.warmup, 10))
             tf = w2.fwd_flop / (f_ms * 1e-3) / 1e12
             pk = PEAK_BF16_TFLOPS if rb.kernel_name(r2.p, False) == "mfma-bf16" else PEAK_F32_VALU_TFLOPS
             table[name] = {"fwd_ms": round(f_ms, 4), "fwd_tflops": round(tf, 2),

@@ -10,7 +10,8 @@ reduction).  The default workload is config 5 of the benchmark spec (fwd+bwd, bf16,
 B=16, 96x96 grid, 32x32 windows, shift 16).  Inputs are resident in HBM before
 the timed region starts.  Prints ONE JSON line.
 
-`--all` adds a `configs` table with forward numbers for every named workload.
+`--all` adds a `configs` table with forward numbers for every named workload and a
+`schedule` table (forward and backward) for the layer shapes of the paper's networks.
 """
 import argparse
 import json
@@ -132,7 +133,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     rb.load()
-    wl = wk.WORKLOADS[a.workload]
+    wl = {**wk.WORKLOADS, **wk.SCHEDULE}[a.workload]
     flags = rb.RIB_FLAG_FORCE_ROW_MAX if a.force_row_max else 0
 
     r = Runner(wl, flags)
@@ -193,6 +194,17 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["configs"] = table
+        sched = {}
+        for name, w2 in wk.SCHEDULE.items():
+            r2 = Runner(w2, flags)
+            _, f_ms, b_ms = time_steps(r2, min(20, max(5, a.steps)), 3)
+            ftf, btf = w2.fwd_flop / (f_ms * 1e-3) / 1e12, w2.bwd_flop / (b_ms * 1e-3) / 1e12
+            sched[name] = {"d": w2.d, "r": w2.r, "window": w2.M, "fwd_ms": round(f_ms, 4), "fwd_tflops": round(ftf, 1),
+                           "bwd_ms": round(b_ms, 4), "bwd_tflops": round(btf, 1),
+                           "kernels": rb.kernel_name(r2.p, False) + "/" + rb.kernel_name(r2.p, True)}
+            del r2
+            torch.cuda.empty_cache()
+        res["schedule"] = sched
 
     if not a.no_cpu_baseline:
         n_units = a.cpu_units or min(wl.n_units, 864)

@@ -31,6 +31,7 @@ rib_status make_geo(const rib_params *p, Geo *g)
     g->tstride = p->token_stride != 0 ? p->token_stride : C;
     g->scale_c = p->scale_c; g->scale_p = p->scale_p;
     g->units = (int64_t)p->B * g->nwx * g->nwy * p->heads;
+    g->inv_m = p->window > 1 ? (uint32_t)((((uint64_t)1 << 32) + p->window - 1) / p->window) : 0xffffffffu;
     // every kernel indexes workgroups with 32-bit block ids and tokens with int
     const int64_t blocks = g->units * ((g->N + 63) / 64);
     if (blocks > 0x7fffffffLL || (int64_t)p->B * p->H * p->W > 0x7fffffffLL ||

@@ -18,6 +18,7 @@ struct Geo {
     int64_t tstride;  // elements between consecutive tokens of q, k, v
     float scale_c, scale_p;
     int64_t units;    // B*nwy*nwx*heads (window, head) pairs
+    uint32_t inv_m;   // ceil(2^32 / M): n / M == mulhi(n, inv_m) for every n < 2^24 (M >= 2)
 };
 
 using bf16_t = uint16_t;  // raw bf16 storage
@@ -79,6 +80,54 @@ __device__ __forceinline__ void fill_tok_table(const Geo &g, int w, int *tok, in
             ++iy;
         }
     }
+}
+
+// The same map in separable form, 2*M integers instead of N: grid token of window-local
+// token n = iy*M + ix is rowb[iy] + colo[ix] (row base of the wrapped pixel row, wrapped
+// pixel column).  Large windows (N = 9216) would otherwise spend 36 KB of LDS on the table.
+// Indexing syntax matches the plain table so that code can be written for either.
+struct TokMap {
+    const int *rowb, *colo;
+    uint32_t inv_m;
+    int M;
+    __device__ __forceinline__ int operator[](int n) const
+    {
+        const int iy = (int)__umulhi((uint32_t)n, inv_m);
+        return rowb[iy] + colo[n - iy * M];
+    }
+    // tokens n0 .. n0+3 of one window row (n0 a multiple of 4, M a multiple of 4)
+    __device__ __forceinline__ void quad(int n0, int (&t)[4]) const
+    {
+        const int iy = (int)__umulhi((uint32_t)n0, inv_m);
+        const int rb = rowb[iy];
+        const int4 c = *(const int4 *)(colo + (n0 - iy * M));
+        t[0] = rb + c.x, t[1] = rb + c.y, t[2] = rb + c.z, t[3] = rb + c.w;
+    }
+};
+
+// Fills lds[0, 2M) and returns the map; the caller synchronises the workgroup.  `lds` must be
+// 16-byte aligned and M a multiple of 4 for quad().
+template <int NT>
+__device__ __forceinline__ TokMap fill_tok_map(const Geo &g, int w, int *lds)
+{
+    const int wx = w % g.nwx, t = w / g.nwx, wy = t % g.nwy, b = t / g.nwy;
+    for (int i = threadIdx.x; i < 2 * g.M; i += NT) {
+        if (i < g.M) {
+            int y = wy * g.M + g.s + i;
+            if (y >= g.H) y -= g.H;
+            lds[i] = (b * g.H + y) * g.W;
+        } else {
+            int x = wx * g.M + g.s + (i - g.M);
+            if (x >= g.W) x -= g.W;
+            lds[i] = x;
+        }
+    }
+    TokMap m;
+    m.rowb = lds;
+    m.colo = lds + g.M;
+    m.inv_m = g.inv_m;
+    m.M = g.M;
+    return m;
 }
 
 // Launchers (each returns the hipError_t of its launches).

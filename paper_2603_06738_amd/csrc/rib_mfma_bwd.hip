@@ -507,7 +507,8 @@ struct LayT {
     static constexpr int XT = XR + T * XS;
     static constexpr int YR = XT + 64 * TS;
     static constexpr int YT = YR + T * YS;
-    static constexpr int STAGE = YT + 32 * TS;
+    static constexpr int EX = YT + 32 * TS;          // 2*T floats: -LSE*log2(e), -delta of the tile's queries
+    static constexpr int STAGE = EX + 4 * T;
     static constexpr int KS = DQK / 16, VS = DVK / 16;
 };
 
@@ -580,14 +581,16 @@ __device__ __forceinline__ FConst<DQK, DVK, T> fconst(const Geo &g, int hd, int 
 // extras = LSE, delta.  Otherwise X = k, Y = v (both strided).
 template <int DQK, int DVK, int T, bool QDO>
 __device__ __forceinline__ void fload(FRegs<DQK, DVK> &rg, const FConst<DQK, DVK, T> &c, const Geo &g, int64_t u, int tile,
-                                      const int *tok, const char *xb, const char *yb, const char *fbase,
+                                      const TokMap &tok, const char *xb, const char *yb, const char *fbase,
                                       const float *__restrict__ lse, const float *__restrict__ delta)
 {
     constexpr int kT = T;
     const char *fb = fbase + (uint32_t)tile * (uint32_t)kT * c.frow;
+    int tq[4];
+    tok.quad(tile * kT + c.tok_idx, tq);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-        const uint32_t t = (uint32_t)tok[tile * kT + c.tok_idx + p];
+        const uint32_t t = (uint32_t)tq[p];
         rg.xc[p] = *(const uint32_t *)(xb + (__umul24(t, c.tsb) + c.lane_c));
         rg.yc[p] = *(const uint32_t *)(yb + (__umul24(t, QDO ? c.dsb : c.tsb) + c.lane_c));
         const uint32_t row = (uint32_t)(c.tok_idx + p) * c.frow;
@@ -613,7 +616,7 @@ __device__ __forceinline__ void store_t4(bf16_t *dst, const uint32_t (&w)[4])
     *(uint2 *)(dst + kTS) = odd;
 }
 
-template <int DQK, int DVK, int T, bool QDO, bool TRANS_Y, bool SCALE>
+template <int DQK, int DVK, int T, bool QDO, bool TRANS_Y, bool SCALE, bool XC>
 __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<DQK, DVK, T> &c, bf16_t *S, float sc, float sp)
 {
     using L = LayT<DQK, DVK, T>;
@@ -638,7 +641,13 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
     store_t4<kTS>(S + c.ft0, fa);
     if (DQK == 64) store_t4<kTS>(S + c.ft1, fb);
     if (TRANS_Y) store_t4<kTS>(S + c.yt, rg.yc);
-    if (threadIdx.x < kT) {
+    if (XC) {
+        if (QDO && threadIdx.x < kT) {
+            float *ex = (float *)(S + L::EX);
+            ex[threadIdx.x] = -rg.e0 * kLog2e;
+            ex[kT + threadIdx.x] = -rg.e1;
+        }
+    } else if (threadIdx.x < kT) {
         uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
         if (QDO) {
             ex = split_bf16(-rg.e0 * kLog2e);
@@ -651,8 +660,8 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
 
 // Each wave stages its own 64 stationary rows (X rows [64][XS], Y rows [64][YS], extras
 // included) into its private LDS area `W` and reads them back as MFMA B operands.
-template <int DQK, int DVK, bool QDO, bool SCALE>
-__device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u, int n0, const int *tok, const char *xb,
+template <int DQK, int DVK, bool QDO, bool SCALE, bool XC>
+__device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u, int n0, const TokMap &tok, const char *xb,
                                                 const char *yb, const bf16_t *f, const float *__restrict__ lse,
                                                 const float *__restrict__ delta, float sc, float sp, bf16_t *W,
                                                 bf16x8 (&Xb)[2][DQK / 16], bf16x8 (&Yb)[2][DVK / 16])
@@ -677,7 +686,7 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
         if (DQK == 64) fb2[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f1);
     }
     float e0 = 0.f, e1 = 0.f;
-    if (QDO) {
+    if (QDO && !XC) {
         e0 = lse[u * g.N + n0 + lane];
         e1 = delta[u * g.N + n0 + lane];
     }
@@ -695,7 +704,7 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
         if (DQK == 64) *(uint32_t *)(Xs + row * L::XS + g.d + 2 * f1) = b2;
         *(uint32_t *)(Ys + row * L::YS + 2 * pair) = yy[p];
     }
-    {
+    if (!XC) {
         uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
         if (QDO) {
             ex = split_bf16(-e0 * kLog2e);
@@ -718,7 +727,7 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
 // tokens in a private LDS area -- content columns as bf16 rows of kORS elements, RIB
 // columns as fp32 rows of kFRS elements (odd dword strides: conflict-free both ways) --
 // and writes them out with 16 lanes per token.
-constexpr int kORS = 34, kFRS = 33;
+constexpr int kORS = 34, kFRS = 35;     // kFRS: up to 34 RIB columns (d = 30, r = 34)
 constexpr int kWaveOut = 64 * kORS * 2 + 64 * kFRS * 4;      // bytes per wave
 
 __device__ __forceinline__ void stash_aug(const f32x16 &acc, int mb, int hf, const Geo &g, float sc, float sp,
@@ -736,7 +745,7 @@ __device__ __forceinline__ void stash_aug(const f32x16 &acc, int mb, int hf, con
 }
 
 // rows [n0, n0+64) of a grid tensor from the wave's bf16 area
-__device__ __forceinline__ void flush_rows(const bf16_t *Os, bf16_t *__restrict__ dst, const int *tok, int n0, int hd,
+__device__ __forceinline__ void flush_rows(const bf16_t *Os, bf16_t *__restrict__ dst, const TokMap &tok, int n0, int hd,
                                            const Geo &g)
 {
     const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
@@ -758,6 +767,7 @@ __device__ __forceinline__ void flush_partial(const float *Fs, float *__restrict
         const int row = p * 4 + sub;
         if (j < r) part[row * r + j] = Fs[row * kFRS + j];
         if (16 + j < r) part[row * r + 16 + j] = Fs[row * kFRS + 16 + j];
+        if (32 + j < r) part[row * r + 32 + j] = Fs[row * kFRS + 32 + j];
     }
 }
 
@@ -790,8 +800,8 @@ __device__ __forceinline__ void block_coords(const Geo &g, int nblk, int64_t &u,
 }
 
 // dQ (+ dF_q partial), fast path.
-template <int DQK, int DVK, int T, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dq_fast_kernel(
+template <int DQK, int DVK, int T, int WAVES, bool XC>
+__global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_fast_kernel(
     Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
     const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dq, float *__restrict__ dfq_part)
@@ -801,7 +811,6 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
     constexpr int kT = T, kTS = L::TS, kWaves = WAVES, kNT = WAVES * 64, NB = T / 32;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
-    int *tok = (int *)(smem + Sm::ELEMS16);
 
     int64_t u;
     int blk, w, hd;
@@ -810,7 +819,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
     const int ntiles = g.N / kT;
     const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
 
-    fill_tok_table<kNT>(g, w, tok, g.N);
+    const TokMap tok = fill_tok_map<kNT>(g, w, (int *)(smem + Sm::ELEMS16));
     zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
 
@@ -822,13 +831,13 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
 
     const int q0 = (blk * kWaves + wave) * 64;
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
-    stationary_rows<DQK, DVK, true, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
+    stationary_rows<DQK, DVK, true, true, XC>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
                                     smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb);
     // No second clearing: from here on the padding columns of a streamed tile may hold stale
     // (finite) rows of this workgroup; they only ever multiply the zero padding of the
     // stationary operands, and stale transposed rows only feed accumulator rows that are
     // never stored.
-    fstore<DQK, DVK, T, false, false, false>(rg, c, stage0, 1.f, 1.f);
+    fstore<DQK, DVK, T, false, false, false, XC>(rg, c, stage0, 1.f, 1.f);
     fload<DQK, DVK, T, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
     __syncthreads();
 
@@ -839,6 +848,16 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[qb][mb][i] = 0.f;
+    // XC: a lane owns one query per block, so -LSE*log2(e) and -delta are two lane constants
+    // added to the finished scores.
+    float nl[2] = {0.f, 0.f}, nd[2] = {0.f, 0.f};
+    if (XC) {
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            nl[qb] = -lse[u * g.N + q0 + qb * 32 + col] * kLog2e;
+            nd[qb] = -delta[u * g.N + q0 + qb * 32 + col];
+        }
+    }
 
     for (int tile = 0; tile < ntiles; ++tile) {
         bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
@@ -861,8 +880,14 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
                 for (int t = 0; t < L::VS; ++t) D = mfma(Av[t], Gb[qb][t], D);
                 uint32_t wds[8];
 #pragma unroll
-                for (int i = 0; i < 16; i += 2)
-                    wds[i >> 1] = trunc_pack(__builtin_amdgcn_exp2f(S[i]) * D[i], __builtin_amdgcn_exp2f(S[i + 1]) * D[i + 1]);
+                for (int i = 0; i < 16; i += 2) {
+                    if (XC)
+                        wds[i >> 1] = trunc_pack(__builtin_amdgcn_exp2f(S[i] + nl[qb]) * (D[i] + nd[qb]),
+                                                 __builtin_amdgcn_exp2f(S[i + 1] + nl[qb]) * (D[i + 1] + nd[qb]));
+                    else
+                        wds[i >> 1] = trunc_pack(__builtin_amdgcn_exp2f(S[i]) * D[i],
+                                                 __builtin_amdgcn_exp2f(S[i + 1]) * D[i + 1]);
+                }
                 const bf16x8 B0 = as_bf16x8(wds[0], wds[1], wds[2], wds[3]);
                 const bf16x8 B1 = as_bf16x8(wds[4], wds[5], wds[6], wds[7]);
 #pragma unroll
@@ -872,7 +897,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
                 }
             }
         }
-        fstore<DQK, DVK, T, false, false, false>(rg, c, nxt, 1.f, 1.f);
+        fstore<DQK, DVK, T, false, false, false, XC>(rg, c, nxt, 1.f, 1.f);
         fload<DQK, DVK, T, false>(rg, c, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, kb, vb, fkb, lse, delta);
         __syncthreads();
     }
@@ -892,8 +917,8 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
 }
 
 // dK, dV (+ dF_k partial), fast path.
-template <int DQK, int DVK, int T, int WAVES>
-__global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bwd_dkv_fast_kernel(
+template <int DQK, int DVK, int T, int WAVES, bool XC>
+__global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_fast_kernel(
     Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
     const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
     const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dk, bf16_t *__restrict__ dv,
@@ -904,7 +929,6 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
     constexpr int kT = T, kTS = L::TS, kWaves = WAVES, kNT = WAVES * 64, NB = T / 32;
     extern __shared__ __attribute__((aligned(16))) bf16_t smem[];
     bf16_t *stage0 = smem, *stage1 = smem + L::STAGE;
-    int *tok = (int *)(smem + Sm::ELEMS16);
 
     int64_t u;
     int blk, w, hd;
@@ -913,7 +937,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
     const int ntiles = g.N / kT;
     const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
 
-    fill_tok_table<kNT>(g, w, tok, g.N);
+    const TokMap tok = fill_tok_map<kNT>(g, w, (int *)(smem + Sm::ELEMS16));
     zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
 
@@ -925,9 +949,9 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
 
     const int k0 = (blk * kWaves + wave) * 64;
     bf16x8 Kb[2][L::KS], Vb[2][L::VS];
-    stationary_rows<DQK, DVK, false, true>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, sc2, sp2,
+    stationary_rows<DQK, DVK, false, true, XC>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, sc2, sp2,
                                      smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
-    fstore<DQK, DVK, T, true, true, false>(rg, c, stage0, sc2, sp2);
+    fstore<DQK, DVK, T, true, true, false, XC>(rg, c, stage0, sc2, sp2);
     fload<DQK, DVK, T, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
     __syncthreads();
 
@@ -946,19 +970,38 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         bf16_t *cur = (tile & 1) ? stage1 : stage0, *nxt = (tile & 1) ? stage0 : stage1;
 #pragma unroll
         for (int qb = 0; qb < NB; ++qb) {
+            // With 64 augmented columns the registers are short: the transposed operands are then
+            // read per key block, right where they are used, instead of once per query block.
+            constexpr bool kLate = DQK == 64;
             bf16x8 Aq[L::KS], Ag[L::VS], Aqt[2][2], Agt[2];
             read_rows<L::KS>(Aq, cur + L::XR, L::XS, qb * 32 + col, hf);
             read_rows<L::VS>(Ag, cur + L::YR, L::YS, qb * 32 + col, hf);
+            if (!kLate) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                Agt[t] = *(const bf16x8 *)(cur + L::YT + col * kTS + qb * 32 + 16 * t + 8 * hf);
+                for (int t = 0; t < 2; ++t) {
+                    Agt[t] = *(const bf16x8 *)(cur + L::YT + col * kTS + qb * 32 + 16 * t + 8 * hf);
 #pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-                    Aqt[mb][t] = *(const bf16x8 *)(cur + L::XT + (32 * mb + col) * kTS + qb * 32 + 16 * t + 8 * hf);
+                    for (int mb = 0; mb < 2; ++mb)
+                        Aqt[mb][t] = *(const bf16x8 *)(cur + L::XT + (32 * mb + col) * kTS + qb * 32 + 16 * t + 8 * hf);
+                }
             }
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 f32x16 S = {0}, D = {0};
+                if (XC) {
+                    // accumulator row 8j + 4*hf + e is query qb*32 + that: four consecutive floats per j
+                    // (offset made opaque so that the reads are repeated per key block instead of
+                    // being kept in 32 registers across both)
+                    int exo = qb * 32 + 4 * hf;
+                    asm volatile("" : "+v"(exo));
+                    const float *ex = (const float *)(cur + L::EX) + exo;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float4 a = *(const float4 *)(ex + 8 * j), b = *(const float4 *)(ex + kT + 8 * j);
+                        S[4 * j] = a.x, S[4 * j + 1] = a.y, S[4 * j + 2] = a.z, S[4 * j + 3] = a.w;
+                        D[4 * j] = b.x, D[4 * j + 1] = b.y, D[4 * j + 2] = b.z, D[4 * j + 3] = b.w;
+                    }
+                }
 #pragma unroll
                 for (int t = 0; t < L::KS; ++t) S = mfma(Aq[t], Kb[kb][t], S);
 #pragma unroll
@@ -969,6 +1012,17 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
                     const float p0 = __builtin_amdgcn_exp2f(S[i]), p1 = __builtin_amdgcn_exp2f(S[i + 1]);
                     wp[i >> 1] = trunc_pack(p0, p1);
                     wds[i >> 1] = trunc_pack(p0 * D[i], p1 * D[i + 1]);
+                }
+                if (kLate) {
+                    int to = qb * 32 + 8 * hf + col * kTS;
+                    asm volatile("" : "+v"(to));
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        Agt[t] = *(const bf16x8 *)(cur + L::YT + to + 16 * t);
+#pragma unroll
+                        for (int mb = 0; mb < 2; ++mb)
+                            Aqt[mb][t] = *(const bf16x8 *)(cur + L::XT + 32 * mb * kTS + to + 16 * t);
+                    }
                 }
                 accV[kb] = mfma(Agt[0], as_bf16x8(wp[0], wp[1], wp[2], wp[3]), accV[kb]);
                 accV[kb] = mfma(Agt[1], as_bf16x8(wp[4], wp[5], wp[6], wp[7]), accV[kb]);
@@ -983,7 +1037,7 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
         }
         {
             const FConst<DQK, DVK, T> cc = fconst<DQK, DVK, T>(g, hd, opaque_tid());
-            fstore<DQK, DVK, T, true, true, false>(rg, cc, nxt, sc2, sp2);
+            fstore<DQK, DVK, T, true, true, false, XC>(rg, cc, nxt, sc2, sp2);
             fload<DQK, DVK, T, true>(rg, cc, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, qb_, gb_, fqb, lse,
                                      delta);
         }
@@ -1019,20 +1073,20 @@ __global__ __launch_bounds__(WAVES * 64, (DQK == 48 && DVK == 32) ? 2 : 1) void 
 static bool bwd_fast_ok(const Geo &g)
 {
     const int64_t tokens = (int64_t)g.B * g.H * g.W;
-    return g.r > 0 && g.N % 256 == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+    return g.r > 0 && g.r < kFRS && g.N % 256 == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
            tokens * g.tstride * 2 < ((int64_t)1 << 32);
 }
 
 // Launch the fast pair with workgroups of WAVES waves and streamed tiles of T tokens.
-template <int DQK, int DVK, int T, int WAVES>
+template <int DQK, int DVK, int T, int WAVES, bool XC>
 hipError_t launch_fast(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
                        const void *dout, const float *lse, const float *delta, void *dq, void *dk, void *dv, float *pq,
                        float *pk, hipStream_t st)
 {
-    const size_t smem = FSmem<DQK, DVK, T, WAVES>::BYTES + (size_t)g.N * sizeof(int);
+    const size_t smem = FSmem<DQK, DVK, T, WAVES>::BYTES + (size_t)2 * g.M * sizeof(int);
     if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
-    auto kdkv = mfma_bwd_dkv_fast_kernel<DQK, DVK, T, WAVES>;
-    auto kdq = mfma_bwd_dq_fast_kernel<DQK, DVK, T, WAVES>;
+    auto kdkv = mfma_bwd_dkv_fast_kernel<DQK, DVK, T, WAVES, XC>;
+    auto kdq = mfma_bwd_dq_fast_kernel<DQK, DVK, T, WAVES, XC>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [kdkv, kdq] {
@@ -1053,7 +1107,7 @@ hipError_t launch_fast(const Geo &g, const void *q, const void *k, const void *v
     return hipGetLastError();
 }
 
-template <int DQK, int DVK>
+template <int DQK, int DVK, bool XC = false>
 hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
                   const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv, float *dfq,
                   float *dfk, void *ws, hipStream_t st)
@@ -1069,10 +1123,11 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     if (bwd_fast_ok(g)) {
         // (workgroups of 8 waves with 128-token tiles -- launch_fast<DQK, DVK, 128, 8> -- were
         // measured slower: one workgroup per CU leaves the prologue's memory latency uncovered)
-        e = launch_fast<DQK, DVK, 64, 4>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
+        e = launch_fast<DQK, DVK, 64, 4, XC>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
         if (e != hipSuccess) return e;
         return launch_reduce_df(g, pq, pk, dfq, dfk, st);
     }
+    if constexpr (XC) return hipErrorInvalidValue;   // the general kernels carry the extras in columns only
 
     const int ntiles = (g.N + kT - 1) / kT;
     const int nblk = (ntiles + kWaves - 1) / kWaves;
@@ -1104,16 +1159,32 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
 
 }  // namespace
 
+// -LSE and -delta ride either in two spare padding columns of the augmented operands (free
+// when d+r+2 and d+2 round up to the same MFMA K multiples as d+r and d) or, on the fast
+// path, in the C operand of the score MFMAs, which needs no columns at all: d+r may then
+// fill all 64 columns (the paper's r = 34 with d = 30, r = 32 with d = 32) and d all 32.
+static bool columns_are_free(const Geo &g)
+{
+    const int a = g.d + g.r;
+    return g.d + 2 <= 32 && (a + 2 <= 48 || (a > 48 && a + 2 <= 64));
+}
+
 bool mfma_bwd_supported(const Geo &g, int dtype)
 {
-    return dtype == RIB_BF16 && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 && g.d + g.r + 2 <= 64 && g.N >= 64 &&
-           g.N <= 9216 && (g.tstride & 1) == 0;
+    if (!(dtype == RIB_BF16 && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 && g.N >= 64 && g.N <= 9216 &&
+          (g.tstride & 1) == 0))
+        return false;
+    return bwd_fast_ok(g) ? g.d + g.r <= 64 : g.d + g.r + 2 <= 64;
 }
 
 hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
                            const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv,
                            float *dfq, float *dfk, void *ws, hipStream_t st)
 {
+    if (bwd_fast_ok(g) && !columns_are_free(g)) {
+        if (g.d + g.r <= 48) return launch<48, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
+        return launch<64, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
+    }
     const bool small_qk = g.d + g.r + 2 <= 48, small_v = g.d + 2 <= 32;
     if (small_qk && small_v) return launch<48, 32>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
     if (small_v) return launch<64, 32>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);

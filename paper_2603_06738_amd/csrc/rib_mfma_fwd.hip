@@ -95,8 +95,8 @@ struct Stage {
 
 // Issue the global loads of one 64-token tile (tile index `tile` of tensor x / y,
 // RIB table f) into registers.  Tokens past N read nothing and yield zeros.
-template <int DQK, int WAVES, bool WITH_V>
-__device__ __forceinline__ void tile_load(Stage<DQK, WAVES> &st, const Geo &g, int hd, int tile, const int *tok,
+template <int DQK, int WAVES, bool WITH_V, class TK>
+__device__ __forceinline__ void tile_load(Stage<DQK, WAVES> &st, const Geo &g, int hd, int tile, const TK &tok,
                                           const bf16_t *__restrict__ x, const bf16_t *__restrict__ y,
                                           const bf16_t *__restrict__ f)
 {
@@ -162,8 +162,8 @@ __device__ __forceinline__ void tile_store(const Stage<DQK, WAVES> &st, const Ge
 }
 
 // One pass of a wave's 64 queries over all keys of the unit.
-template <int DQK, int WAVES, bool ONES, bool TRACK_MAX>
-__device__ __forceinline__ void attend(const Geo &g, int hd, const int *tok, bf16_t (*Ka)[kTK * (DQK + 8)],
+template <int DQK, int WAVES, bool ONES, bool TRACK_MAX, class TK>
+__device__ __forceinline__ void attend(const Geo &g, int hd, const TK &tok, bf16_t (*Ka)[kTK * (DQK + 8)],
                                        bf16_t (*Vt)[32 * kVStr], const int *foff, const bf16x8 (&Q)[2][DQK / 16],
                                        const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
                                        const bf16_t *__restrict__ fk, f32x16 (&O)[2], float (&mrun)[2], float (&lsum)[2])
@@ -347,17 +347,22 @@ __device__ __forceinline__ FastConst<DQK> fast_const(const Geo &g, int hd)
     return c;
 }
 
-// global loads of token p (0..3) of this lane's group
+// global loads of this lane's four tokens of the tile that starts at window-local token n0
 template <int DQK>
-__device__ __forceinline__ void fast_load(FastRegs<DQK> &rg, const FastConst<DQK> &c, const Geo &g, int p, const int *tokt,
+__device__ __forceinline__ void fast_load(FastRegs<DQK> &rg, const FastConst<DQK> &c, const Geo &g, const TokMap &tok, int n0,
                                           const char *kb, const char *vb, const char *fb)
 {
-    const uint32_t off = __umul24((uint32_t)tokt[c.tok_idx + p], c.tsb) + c.lane_c;
-    rg.kx[p] = *(const dword2 *)(kb + off);
-    rg.vx[p] = *(const dword2 *)(vb + off);
-    const uint32_t row = (uint32_t)(c.tok_idx + p) * (uint32_t)(g.r * 2);
-    rg.fa[p] = *(const dword2 *)(fb + row + c.f_off0);
-    if (DQK == 64) rg.fb[p] = *(const dword2 *)(fb + row + c.f_off1);
+    int t[4];
+    tok.quad(n0 + c.tok_idx, t);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t off = __umul24((uint32_t)t[p], c.tsb) + c.lane_c;
+        rg.kx[p] = *(const dword2 *)(kb + off);
+        rg.vx[p] = *(const dword2 *)(vb + off);
+        const uint32_t row = (uint32_t)(c.tok_idx + p) * (uint32_t)(g.r * 2);
+        rg.fa[p] = *(const dword2 *)(fb + row + c.f_off0);
+        if (DQK == 64) rg.fb[p] = *(const dword2 *)(fb + row + c.f_off1);
+    }
 }
 
 // LDS writes of token p: its pieces of the K_aug row; after the 4th token the four V^T
@@ -406,7 +411,7 @@ __device__ __forceinline__ FastCtx<DQK> fast_ctx(const Geo &g, int hd, const bf1
 
 // `rg` holds tile 0 (its global loads were issued by the caller, early).
 template <int DQK, bool ONES>
-__device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx, FastRegs<DQK> &rg, const int *tok,
+__device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx, FastRegs<DQK> &rg, const TokMap &tok,
                                             bf16_t *Kf, bf16_t *Vf, const bf16x8 (&Q)[2][DQK / 16], f32x16 (&O)[2],
                                             float (&lsum)[2])
 {
@@ -428,9 +433,7 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
     for (int p = 0; p < 4; ++p) fast_store<DQK>(rg, c, p, Kf, Vf);
     {   // tile 1 goes in flight now and is written to LDS at the end of tile 0's block
         const int t1 = ntiles > 1 ? 1 : 0;
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-            fast_load<DQK>(rg, c, g, p, tok + t1 * kFT, kbase, vbase, fbase + (uint32_t)t1 * ftile);
+        fast_load<DQK>(rg, c, g, tok, t1 * kFT, kbase, vbase, fbase + (uint32_t)t1 * ftile);
     }
     __syncthreads();
 
@@ -442,7 +445,6 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
         // `rg` holds tile+1 (requested one block ago); tile+2 is requested at the end of this
         // block.  Past the end both clamp to the last tile (staged again, never used).
         const int nt = tile + 2 < ntiles ? tile + 2 : ntiles - 1;
-        const int *tokn = tok + nt * kFT;
         const char *fn = fbase + (uint32_t)nt * ftile;
 
         bf16x8 Ak[4][KS], Av[4][2];
@@ -511,8 +513,7 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
         // tile+2 is requested into the same registers
 #pragma unroll
         for (int p = 0; p < 4; ++p) fast_store<DQK>(rg, c, p, Kn, Vn);
-#pragma unroll
-        for (int p = 0; p < 4; ++p) fast_load<DQK>(rg, c, g, p, tokn, kbase, vbase, fn);
+        fast_load<DQK>(rg, c, g, tok, nt * kFT, kbase, vbase, fn);
 
         // The order the scheduler is asked to build out of the block above: every MFMA
         // followed by its share of the exp2 (transcendental) and pack (VALU) work.
@@ -688,7 +689,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *tiles = (bf16_t *)smem;
     bf16_t *Kf = tiles, *Vf = tiles + Sm::FAST_K;
-    int *tok = (int *)(smem + Sm::TILE_BYTES);
+    // (window-local token -> grid token, as two tables of M entries)
 
     const int G = gridDim.x, per = G >> 3, rem = G & 7, xcd = blockIdx.x & 7;
     const int logical = xcd * per + (xcd < rem ? xcd : rem) + (blockIdx.x >> 3);
@@ -698,7 +699,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int col = lane & 31, hf = lane >> 5;
 
-    fill_tok_table<NT>(g, w, tok, g.N);
+    const TokMap tok = fill_tok_map<NT>(g, w, (int *)(smem + Sm::TILE_BYTES));
     {   // zero the Q staging area (rows of all four waves): its padding columns must read 0
         uint4 z = {0u, 0u, 0u, 0u};
         for (int e = tid; e < NT * KSTR / 8; e += NT) ((uint4 *)tiles)[e] = z;
@@ -707,8 +708,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
 
     const FastCtx<DQK> fx = fast_ctx<DQK>(g, hd, k, v, fk);
     FastRegs<DQK> rg;
-#pragma unroll
-    for (int p = 0; p < 4; ++p) fast_load<DQK>(rg, fx.c, g, p, tok, fx.kbase, fx.vbase, fx.fbase);
+    fast_load<DQK>(rg, fx.c, g, tok, 0, fx.kbase, fx.vbase, fx.fbase);
 
     // Q_aug rows of this wave: 16 lanes per token, 4 tokens per pass
     const int q0 = blk * NT + wave * 64;
@@ -819,7 +819,7 @@ hipError_t launch(const Geo &g, int force_max, const void *q, const void *k, con
     constexpr int WAVES = 4;
     const int nqblk = (g.N + WAVES * 64 - 1) / (WAVES * 64);
     const int ntiles = (g.N + kTK - 1) / kTK;
-    const size_t dyn = FwdSmem<DQK, FAST>::TILE_BYTES + (size_t)ntiles * kTK * sizeof(int);
+    const size_t dyn = FwdSmem<DQK, FAST>::TILE_BYTES + (FAST ? (size_t)2 * g.M : (size_t)ntiles * kTK) * sizeof(int);
     if (dyn > (size_t)kMaxDynLds) return hipErrorInvalidValue;
     auto kern = FAST ? mfma_fwd_fast_kernel<DQK, ONES> : mfma_fwd_kernel<DQK, WAVES, ONES, false>;
     static std::once_flag once;

@@ -99,6 +99,34 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+def _eq5(name, B, HW, heads, d, r, M, seed):
+    return Workload(name, "bf16", B, HW, HW, heads, d, r, M, 0, 1.0 / float(np.sqrt(d)), 1.0 / float(np.sqrt(r)),
+                    seed, True)
+
+
+# The attention layers of the paper's own networks (Appendix, table "Network implementation
+# details"): window sides cycle per layer and the RIB rank grows in the second cycle.  One
+# entry per distinct (head dim, rank, window) of the "+" variants trained on 96x96 patches,
+# plus the 64-windows of the base variants; no shift (the paper's networks use none), the
+# paper's two scales (Eq. 5), forward + backward, batch 16.
+SCHEDULE: Dict[str, Workload] = {
+    w.name: w for w in [
+        _eq5("sst-m16-r18", 16, 96, 6, 30, 18, 16, _SEED0 + 101),
+        _eq5("sst-m32-r18", 16, 96, 6, 30, 18, 32, _SEED0 + 102),
+        _eq5("sst-m48-r18", 16, 96, 6, 30, 18, 48, _SEED0 + 103),
+        _eq5("sst-m32-r34", 16, 96, 6, 30, 34, 32, _SEED0 + 104),
+        _eq5("sst-m48-r34", 16, 96, 6, 30, 34, 48, _SEED0 + 105),
+        _eq5("sst-m96-r34", 16, 96, 6, 30, 34, 96, _SEED0 + 106),
+        _eq5("sst-m64-r34", 16, 128, 6, 30, 34, 64, _SEED0 + 107),
+        _eq5("sstl-m32-r16", 16, 96, 6, 32, 16, 32, _SEED0 + 111),
+        _eq5("sstl-m48-r32", 16, 96, 6, 32, 32, 48, _SEED0 + 112),
+        _eq5("sstl-m96-r32", 16, 96, 6, 32, 32, 96, _SEED0 + 113),
+        _eq5("light-m48-r16", 16, 96, 3, 16, 16, 48, _SEED0 + 121),
+        _eq5("light-m96-r24", 16, 96, 3, 16, 24, 96, _SEED0 + 122),
+    ]
+}
+
+
 def paper_scales(wl: Workload) -> Workload:
     """Same workload with the paper's own two scales (Eq. 5): 1/sqrt(d) on the
     content part and 1/sqrt(r) on the positional part."""

@@ -35,6 +35,11 @@ def _small_cases():
               scale_c=1 / math.sqrt(30), scale_p=1 / math.sqrt(18)),        # the paper's scales and an SST rank
             c(f"d32r16-{dt}", dt, 1, 32, 32, 2, 32, 16, 32, 16, 211),       # SST-L head, N=1024
             c(f"d30r34-{dt}", dt, 1, 16, 16, 2, 30, 34, 16, 1, 212),        # SST second-cycle rank
+            c(f"d32r32-{dt}", dt, 1, 16, 32, 2, 32, 32, 16, 0, 213),        # SST-L second-cycle rank
+            c(f"d16r24-{dt}", dt, 1, 16, 16, 3, 16, 24, 16, 2, 214),        # SST-light second-cycle rank
+            c(f"d16r16-{dt}", dt, 1, 16, 16, 3, 16, 16, 16, 0, 215),        # SST-light first cycle
+            c(f"d30r18m12-{dt}", dt, 1, 12, 24, 2, 30, 18, 12, 5, 216),     # SST rank on a ragged window
+            c(f"d30r34m12-{dt}", dt, 1, 12, 12, 2, 30, 34, 12, 0, 217),
         ]
     return cases
 
@@ -167,3 +172,22 @@ def test_config5_backward_full_size(oracle, gh):
     tol = gh.TOL[wl.dtype]
     for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
         assert gh.max_abs(a, b) <= tol, name
+
+
+@pytest.mark.parametrize("name", list(wk.SCHEDULE))
+def test_paper_schedule_layers(oracle, gh, name):
+    """The (head dim, rank, window) combinations of the paper's networks (Appendix,
+    "Network implementation details"), with the paper's two scales: forward and
+    backward, every element, on ONE image of the scheduled workload (the kernels'
+    launch shape per window is the benchmark's; the batch only multiplies windows;
+    the 64- and 96-windows keep two heads so that the oracle finishes in seconds)."""
+    from dataclasses import replace
+    wl = replace(wk.SCHEDULE[name], B=1)
+    if wl.M >= 64:
+        wl = replace(wl, heads=2)
+    x = wk.make_inputs(wl)
+    t, out, lse = _check_fwd(oracle, gh, wl, x)
+    got = gh.gpu_bwd(wl, t, out, lse)
+    ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    for nm, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+        assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], nm

@@ -175,3 +175,26 @@ def custom(name, dtype, B, H, W, heads, d, r, M, s, seed, scale_c=None, scale_p=
     return Workload(name, dtype, B, H, W, heads, d, r, M, s,
                     sc if scale_c is None else scale_c,
                     sc if scale_p is None else scale_p, seed, backward)
+
+
+def make_generator_params(heads: int, r: int, L: int = 10, d_h: int = 32, seed: int = _SEED0 + 900) -> Dict[str, np.ndarray]:
+    """Random parameters of the RIB feature generator (paper Sec. 3.1 Eq. 2-3; L = 10 and
+    d_h = 32 are the paper's settings): W_h [2+4L, d_h], b_h [d_h], W_pq, W_pk [heads, d_h, r],
+    float32, drawn in that order from one Philox stream; the standard deviations only keep
+    the generated features at the size of the attention workloads' (about 0.5)."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    n_in = 2 + 4 * L
+    out = {
+        "W_h": rng.standard_normal((n_in, d_h), dtype=np.float32) * np.float32(1.0 / np.sqrt(n_in)),
+        "b_h": rng.standard_normal((d_h,), dtype=np.float32) * np.float32(0.1),
+        "W_pq": rng.standard_normal((heads, d_h, r), dtype=np.float32) * np.float32(0.25),
+        "W_pk": rng.standard_normal((heads, d_h, r), dtype=np.float32) * np.float32(0.25),
+    }
+    return out
+
+
+def make_feature_grads(heads: int, M: int, r: int, seed: int = _SEED0 + 901) -> Dict[str, np.ndarray]:
+    """Upstream gradients df_q, df_k [heads, M*M, r] (float32, N(0,1)) for generator tests."""
+    rng = np.random.Generator(np.random.Philox(key=seed))
+    shape = (heads, M * M, r)
+    return {"df_q": rng.standard_normal(shape, dtype=np.float32), "df_k": rng.standard_normal(shape, dtype=np.float32)}

@@ -100,6 +100,34 @@ def time_steps(r, steps, warmup):
     return wall, fwd, bwd
 
 
+def time_generator(rb, torch, M=96, heads=6, r=34, L=10, d_h=32, reps=20):
+    """RIB feature generator (Eq. 1-3) at the largest window of the paper's schedule: ms per call."""
+    from paper_2603_06738_amd import workloads as wk
+    dev = "cuda:0"
+    w = {k: torch.from_numpy(v).to(dev) for k, v in wk.make_generator_params(heads, r, L, d_h).items()}
+    g = {k: torch.from_numpy(v).to(dev) for k, v in wk.make_feature_grads(heads, M, r).items()}
+    p = rb.make_gen_params(M, heads, r, L, d_h, "bf16")
+    f_q = torch.empty((heads, M * M, r), dtype=torch.bfloat16, device=dev)
+    f_k = torch.empty_like(f_q)
+    grads = [torch.empty_like(w[n]) for n in ("W_h", "b_h", "W_pq", "W_pk")]
+    ws = torch.empty(rb.rib_features_bwd_workspace_bytes(p), dtype=torch.uint8, device=dev)
+    fwd = lambda: rb.rib_features_fwd(p, w["W_h"], w["b_h"], w["W_pq"], w["W_pk"], f_q, f_k)
+    bwd = lambda: rb.rib_features_bwd(p, w["W_h"], w["b_h"], w["W_pq"], w["W_pk"], g["df_q"], g["df_k"], *grads, ws)
+    out = {"window": M, "heads": heads, "r": r, "L": L, "d_h": d_h}
+    for name, fn in (("fwd_ms", fwd), ("bwd_ms", bwd)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = round(e0.elapsed_time(e1) / reps, 4)
+    return out
+
+
 def cpu_baseline(wl, n_units):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -205,6 +233,7 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["schedule"] = sched
+        res["generator"] = time_generator(rb, torch)
 
     if not a.no_cpu_baseline:
         n_units = a.cpu_units or min(wl.n_units, 864)

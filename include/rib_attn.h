@@ -124,6 +124,56 @@ rib_status rib_window_attn_bwd(const rib_params *p,
                                float *df_q, float *df_k,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* ------------------------------------------------------------------------
+ * RIB feature generator (paper Sec. 3.1 Eq. 1-3): produces the f_q, f_k tables
+ * the attention entry points above consume.  For an M x M window every token
+ * n = iy*M + ix has the coordinate pair x = (-1 + 2 iy/(M-1), -1 + 2 ix/(M-1))
+ * (row first; the single token of M = 1 sits at 0), and
+ *
+ *   r_in = [ x, sin(2^0 x), cos(2^0 x), ..., sin(2^(L-1) x), cos(2^(L-1) x) ]   (Eq. 1, width 2+4L)
+ *   h    = ReLU(r_in W_h + b_h)                                                  (Eq. 2, width d_h)
+ *   f_q[head] = h W_pq[head],    f_k[head] = h W_pk[head]                        (Eq. 3, width r)
+ *
+ * h is shared by all heads; the projections are per head and have no bias.
+ * The tables depend only on M and the weights, so a caller computes them once
+ * per weight update and window size (Sec. 3.1, last paragraph).
+ *
+ * Layouts (all dense, row-major, DEVICE pointers): W_h [2+4L][d_h], b_h [d_h],
+ * W_pq, W_pk [heads][d_h][r] -- always fp32; f_q, f_k [heads][M*M][r] in
+ * `dtype` storage (bf16: rounded to nearest even from the fp32 result).
+ * Arithmetic: coordinates and their sines / cosines in fp64, rounded once to
+ * fp32; the two matrix products in fp32. */
+typedef struct rib_gen_params {
+    int32_t window;   /* M, 1..256 */
+    int32_t heads;    /* 1..64 */
+    int32_t r;        /* 1..64 */
+    int32_t L;        /* Fourier bands, 0..16 (paper: 10) */
+    int32_t d_h;      /* hidden width, 1..64 (paper: 32) */
+    int32_t dtype;    /* rib_dtype of f_q, f_k */
+} rib_gen_params;
+
+/* Enqueue the generator forward.  Errors: RIB_ERR_NULL, RIB_ERR_SHAPE (a size
+ * outside the ranges above), RIB_ERR_DTYPE, RIB_ERR_LAUNCH. */
+rib_status rib_features_fwd(const rib_gen_params *p, const float *W_h, const float *b_h,
+                            const float *W_pq, const float *W_pk, void *f_q, void *f_k, void *stream);
+
+/* Bytes of scratch rib_features_bwd needs (a multiple of 256; 0 if *p is invalid). */
+size_t rib_features_bwd_workspace_bytes(const rib_gen_params *p);
+
+/* Enqueue the generator backward: from df_q, df_k [heads][M*M][r] fp32 (what
+ * rib_window_attn_bwd returns, possibly summed over layers that share the
+ * generator) to the gradients of the four weight tensors, fp32, same shapes as
+ * the weights, OVERWRITTEN.  Chain rule through Eq. 3, 2 (ReLU passes the
+ * gradient where its input is positive) and the linear layer of Eq. 2; sums
+ * over tokens run in a fixed order (run-to-run identical results).  `workspace`
+ * is device scratch, 256-byte aligned, at least
+ * rib_features_bwd_workspace_bytes(p) bytes, owned by the caller (else
+ * RIB_ERR_WORKSPACE). */
+rib_status rib_features_bwd(const rib_gen_params *p, const float *W_h, const float *b_h,
+                            const float *W_pq, const float *W_pk, const float *df_q, const float *df_k,
+                            float *dW_h, float *db_h, float *dW_pq, float *dW_pk,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Static, NUL-terminated description of a status code. */
 const char *rib_status_string(rib_status st);
 

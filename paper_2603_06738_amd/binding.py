@@ -21,7 +21,8 @@ STATUS_NAMES = {0: "RIB_OK", 1: "RIB_ERR_NULL", 2: "RIB_ERR_SHAPE", 3: "RIB_ERR_
                 4: "RIB_ERR_UNSUPPORTED", 5: "RIB_ERR_WORKSPACE", 6: "RIB_ERR_LAUNCH"}
 
 EXPORTS = ("rib_window_attn_fwd", "rib_window_attn_bwd", "rib_window_attn_bwd_workspace_bytes",
-           "rib_status_string", "rib_window_attn_kernel_name")
+           "rib_status_string", "rib_window_attn_kernel_name",
+           "rib_features_fwd", "rib_features_bwd", "rib_features_bwd_workspace_bytes")
 
 
 class RibParams(ctypes.Structure):
@@ -32,6 +33,12 @@ class RibParams(ctypes.Structure):
                 ("scale_c", ctypes.c_float), ("scale_p", ctypes.c_float),
                 ("dtype", ctypes.c_int32), ("flags", ctypes.c_int32),
                 ("token_stride", ctypes.c_int64)]
+
+
+class RibGenParams(ctypes.Structure):
+    """Mirror of `rib_gen_params`."""
+    _fields_ = [("window", ctypes.c_int32), ("heads", ctypes.c_int32), ("r", ctypes.c_int32),
+                ("L", ctypes.c_int32), ("d_h", ctypes.c_int32), ("dtype", ctypes.c_int32)]
 
 
 class RibError(RuntimeError):
@@ -64,6 +71,13 @@ def load() -> ctypes.CDLL:
     lib.rib_status_string.argtypes = [ctypes.c_int]
     lib.rib_window_attn_kernel_name.restype = ctypes.c_char_p
     lib.rib_window_attn_kernel_name.argtypes = [pp, ctypes.c_int]
+    gp = ctypes.POINTER(RibGenParams)
+    lib.rib_features_fwd.restype = ctypes.c_int
+    lib.rib_features_fwd.argtypes = [gp] + [vp] * 6 + [vp]
+    lib.rib_features_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.rib_features_bwd_workspace_bytes.argtypes = [gp]
+    lib.rib_features_bwd.restype = ctypes.c_int
+    lib.rib_features_bwd.argtypes = [gp] + [vp] * 10 + [vp, ctypes.c_size_t, vp]
     _lib = lib
     return lib
 
@@ -141,6 +155,46 @@ def rib_window_attn_bwd(p, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q,
                                     workspace, workspace_bytes, stream)
     if st != RIB_OK:
         raise RibError(st, "rib_window_attn_bwd")
+
+
+def make_gen_params(window, heads, r, L=10, d_h=32, dtype="f32") -> RibGenParams:
+    if isinstance(dtype, str):
+        dtype = {"f32": RIB_F32, "bf16": RIB_BF16}[dtype]
+    return RibGenParams(window, heads, r, L, d_h, dtype)
+
+
+def rib_features_fwd_status(p, W_h, b_h, W_pq, W_pk, f_q, f_k, stream=None) -> int:
+    return load().rib_features_fwd(ctypes.byref(p) if p is not None else None, _ptr(W_h), _ptr(b_h), _ptr(W_pq),
+                                   _ptr(W_pk), _ptr(f_q), _ptr(f_k), _stream(stream) if stream != 0 else 0)
+
+
+def rib_features_fwd(p, W_h, b_h, W_pq, W_pk, f_q, f_k, stream=None) -> None:
+    st = rib_features_fwd_status(p, W_h, b_h, W_pq, W_pk, f_q, f_k, stream)
+    if st != RIB_OK:
+        raise RibError(st, "rib_features_fwd")
+
+
+def rib_features_bwd_workspace_bytes(p) -> int:
+    return int(load().rib_features_bwd_workspace_bytes(ctypes.byref(p) if p is not None else None))
+
+
+def rib_features_bwd_status(p, W_h, b_h, W_pq, W_pk, df_q, df_k, dW_h, db_h, dW_pq, dW_pk, workspace,
+                            workspace_bytes=None, stream=None) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else \
+            workspace.numel() * workspace.element_size()
+    return load().rib_features_bwd(ctypes.byref(p) if p is not None else None, _ptr(W_h), _ptr(b_h), _ptr(W_pq),
+                                   _ptr(W_pk), _ptr(df_q), _ptr(df_k), _ptr(dW_h), _ptr(db_h), _ptr(dW_pq),
+                                   _ptr(dW_pk), _ptr(workspace), int(workspace_bytes),
+                                   _stream(stream) if stream != 0 else 0)
+
+
+def rib_features_bwd(p, W_h, b_h, W_pq, W_pk, df_q, df_k, dW_h, db_h, dW_pq, dW_pk, workspace,
+                     workspace_bytes=None, stream=None) -> None:
+    st = rib_features_bwd_status(p, W_h, b_h, W_pq, W_pk, df_q, df_k, dW_h, db_h, dW_pq, dW_pk, workspace,
+                                 workspace_bytes, stream)
+    if st != RIB_OK:
+        raise RibError(st, "rib_features_bwd")
 
 
 # ---- device-memory plumbing for tests, smoke and bench (no arithmetic) --------------------

@@ -410,6 +410,9 @@ __device__ __forceinline__ FastCtx<DQK> fast_ctx(const Geo &g, int hd, const bf1
 }
 
 // `rg` holds tile 0 (its global loads were issued by the caller, early).
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+#define kOnes2 __builtin_bit_cast(bf16x2, 0x3f803f80u)
+
 template <int DQK, bool ONES>
 __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx, FastRegs<DQK> &rg, const TokMap &tok,
                                             bf16_t *Kf, bf16_t *Vf, const bf16x8 (&Q)[2][DQK / 16], f32x16 (&O)[2],
@@ -486,7 +489,10 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
                 // rounding convert.  Numerator and denominator use the same truncated P.
                 const uint32_t w0 = trunc_pack(pe[4 * grp], pe[4 * grp + 1]);
                 const uint32_t w1 = trunc_pack(pe[4 * grp + 2], pe[4 * grp + 3]);
-                if (!ONES) lsum[qb] += (hi_bf16(w0 << 16) + hi_bf16(w0)) + (hi_bf16(w1 << 16) + hi_bf16(w1));
+                if (!ONES) {    // no spare V^T row for the ones: sum the packed pairs with the bf16 dot product
+                    lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w0), kOnes2, lsum[qb], false);
+                    lsum[qb] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w1), kOnes2, lsum[qb], false);
+                }
                 if ((grp & 1) == 0) {
                     P[cs][grp >> 1].x = w0;
                     P[cs][grp >> 1].y = w1;

@@ -97,3 +97,32 @@ def test_backward_workspace_validation():
 def test_kernel_family_names():
     assert rb.kernel_name(good()) is not None
     assert rb.kernel_name(good(), backward=True) is not None
+
+
+def test_generator_params_layout_and_validation():
+    assert ctypes.sizeof(rb.RibGenParams) == 24
+    ok = rb.make_gen_params(16, 6, 18)
+    need = rb.rib_features_bwd_workspace_bytes(ok)
+    assert need > 0 and need % 256 == 0
+    ptrs = [FAKE] * 6
+    for bad in (dict(window=0), dict(window=257), dict(heads=0), dict(r=0), dict(r=65), dict(L=-1), dict(L=17),
+                dict(d_h=0), dict(d_h=65)):
+        kw = dict(window=16, heads=6, r=18, L=10, d_h=32)
+        kw.update(bad)
+        p = rb.make_gen_params(**kw)
+        assert rb.rib_features_fwd_status(p, *ptrs, stream=0) == 2, bad
+        assert rb.rib_features_bwd_workspace_bytes(p) == 0
+    assert rb.rib_features_fwd_status(rb.make_gen_params(16, 6, 18, dtype=5), *ptrs, stream=0) == 3
+    assert rb.rib_features_fwd_status(None, *ptrs, stream=0) == 1
+    for i in range(6):
+        a = list(ptrs)
+        a[i] = None
+        assert rb.rib_features_fwd_status(ok, *a, stream=0) == 1
+    b = [FAKE] * 10
+    assert rb.rib_features_bwd_status(ok, *b, None, need, stream=0) == 5
+    assert rb.rib_features_bwd_status(ok, *b, 0x1000, need - 1, stream=0) == 5
+    assert rb.rib_features_bwd_status(ok, *b, 0x1010, need, stream=0) == 5
+    for i in range(10):
+        a = list(b)
+        a[i] = None
+        assert rb.rib_features_bwd_status(ok, *a, 0x1000, need, stream=0) == 1

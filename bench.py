@@ -128,6 +128,37 @@ def time_generator(rb, torch, M=96, heads=6, r=34, L=10, d_h=32, reps=20):
     return out
 
 
+def time_gated(rb, torch, wl, reps=30):
+    """The same step with the CLA gate (Eq. 9) fused into the forward epilogue and the delta pass."""
+    from paper_2603_06738_amd import workloads as wk
+    r = Runner(wl)
+    gate = rb.to_device(wk.make_gate(wl), wl.dtype)
+    out_g, dgate = torch.empty_like(r.out), torch.empty_like(r.out)
+    ws = torch.empty(rb.rib_window_attn_gated_bwd_workspace_bytes(r.p), dtype=torch.uint8, device="cuda:0")
+    t = r.t
+
+    def fwd():
+        rb.rib_window_attn_gated_fwd(r.p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], gate, out_g, r.out, r.lse)
+
+    def bwd():
+        rb.rib_window_attn_gated_bwd(r.p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], gate, r.out, t["d_out"], r.lse,
+                                     r.dq, r.dk, r.dv, dgate, r.dfq, r.dfk, ws)
+
+    res = {}
+    for name, fn in (("fwd_ms", fwd), ("bwd_ms", bwd)):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(e0.elapsed_time(e1) / reps, 4)
+    return res
+
+
 def cpu_baseline(wl, n_units):
     """The CPU oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -234,6 +265,7 @@ def main():
             torch.cuda.empty_cache()
         res["schedule"] = sched
         res["generator"] = time_generator(rb, torch)
+        res["gated_c5"] = time_gated(rb, torch, wk.WORKLOADS["c5"])
 
     if not a.no_cpu_baseline:
         n_units = a.cpu_units or min(wl.n_units, 864)

@@ -125,6 +125,39 @@ rib_status rib_window_attn_bwd(const rib_params *p,
                                void *workspace, size_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
+ * Gated variants: the convolutional-local-attention gate of the paper's Sec. 3.2
+ * Eq. 9, O' = O (.) G, applied in the attention kernel's epilogue instead of in
+ * a separate elementwise pass (the convolutions and the sigmoid that produce G,
+ * Eq. 8, stay with the caller).  `gate` is a dense [B][H][W][C] tensor in the
+ * problem's storage type, in ORIGINAL grid coordinates like q, k, v.
+ *
+ * Forward: out_gated = O (.) gate.  out_raw (may be NULL for inference) receives
+ * the ungated O, which the backward needs.  Everything else as
+ * rib_window_attn_fwd. */
+rib_status rib_window_attn_gated_fwd(const rib_params *p,
+                                     const void *q, const void *k, const void *v,
+                                     const void *f_q, const void *f_k, const void *gate,
+                                     void *out_gated, void *out_raw, float *lse, void *stream);
+
+/* Scratch bytes for rib_window_attn_gated_bwd (the plain backward's scratch plus
+ * one grid tensor for dO; a multiple of 256, 0 if *p is invalid). */
+size_t rib_window_attn_gated_bwd_workspace_bytes(const rib_params *p);
+
+/* Backward of the gated operator from d_out_gated = dL/dO':
+ *     dO = dO' (.) G    (formed once, in the storage type, inside the workspace)
+ *     dG = dO' (.) O    (written to dgate, [B][H][W][C], storage type)
+ * followed by the backward of the plain operator with that dO; one pass over the
+ * grid produces dO, dG and delta together.  out_raw is the UNGATED forward
+ * output.  Arguments, errors and determinism otherwise as rib_window_attn_bwd. */
+rib_status rib_window_attn_gated_bwd(const rib_params *p,
+                                     const void *q, const void *k, const void *v,
+                                     const void *f_q, const void *f_k, const void *gate,
+                                     const void *out_raw, const void *d_out_gated, const float *lse,
+                                     void *dq, void *dk, void *dv, void *dgate,
+                                     float *df_q, float *df_k,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
  * RIB feature generator (paper Sec. 3.1 Eq. 1-3): produces the f_q, f_k tables
  * the attention entry points above consume.  For an M x M window every token
  * n = iy*M + ix has the coordinate pair x = (-1 + 2 iy/(M-1), -1 + 2 ix/(M-1))

@@ -156,3 +156,20 @@ def unit_token_index(g: Geometry, unit: int):
     y = (wy * g.M + n // g.M + g.s) % g.H
     x = (wx * g.M + n % g.M + g.s) % g.W
     return b, y, x, hd
+
+
+def gated_fwd(g: Geometry, q, k, v, f_q, f_k, gate):
+    """Forward with the convolutional-local-attention gate of the paper's Eq. 9 applied to the
+    result: returns (O' = O * G, O, LSE), all float64; `gate` is a [B,H,W,C] grid."""
+    O, lse = fwd(g, q, k, v, f_q, f_k)
+    return O * np.asarray(gate, np.float64), O, lse
+
+
+def gated_bwd(g: Geometry, q, k, v, f_q, f_k, gate, d_out_gated):
+    """Backward of gated_fwd for the upstream gradient of O': product rule through Eq. 9
+    (dO = dO' * G, dG = dO' * O), then the plain backward.  Returns
+    (dQ, dK, dV, dF_q, dF_k, dG)."""
+    O, _ = fwd(g, q, k, v, f_q, f_k)
+    up = np.asarray(d_out_gated, np.float64)
+    d_out = up * np.asarray(gate, np.float64)
+    return (*bwd(g, q, k, v, f_q, f_k, d_out.astype(np.float32)), up * O)

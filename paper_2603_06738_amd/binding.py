@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "RIB_OK", 1: "RIB_ERR_NULL", 2: "RIB_ERR_SHAPE", 3: "RIB_ERR_
 
 EXPORTS = ("rib_window_attn_fwd", "rib_window_attn_bwd", "rib_window_attn_bwd_workspace_bytes",
            "rib_status_string", "rib_window_attn_kernel_name",
-           "rib_features_fwd", "rib_features_bwd", "rib_features_bwd_workspace_bytes")
+           "rib_features_fwd", "rib_features_bwd", "rib_features_bwd_workspace_bytes",
+           "rib_window_attn_gated_fwd", "rib_window_attn_gated_bwd", "rib_window_attn_gated_bwd_workspace_bytes")
 
 
 class RibParams(ctypes.Structure):
@@ -71,6 +72,12 @@ def load() -> ctypes.CDLL:
     lib.rib_status_string.argtypes = [ctypes.c_int]
     lib.rib_window_attn_kernel_name.restype = ctypes.c_char_p
     lib.rib_window_attn_kernel_name.argtypes = [pp, ctypes.c_int]
+    lib.rib_window_attn_gated_fwd.restype = ctypes.c_int
+    lib.rib_window_attn_gated_fwd.argtypes = [pp] + [vp] * 9 + [vp]
+    lib.rib_window_attn_gated_bwd_workspace_bytes.restype = ctypes.c_size_t
+    lib.rib_window_attn_gated_bwd_workspace_bytes.argtypes = [pp]
+    lib.rib_window_attn_gated_bwd.restype = ctypes.c_int
+    lib.rib_window_attn_gated_bwd.argtypes = [pp] + [vp] * 15 + [vp, ctypes.c_size_t, vp]
     gp = ctypes.POINTER(RibGenParams)
     lib.rib_features_fwd.restype = ctypes.c_int
     lib.rib_features_fwd.argtypes = [gp] + [vp] * 6 + [vp]
@@ -155,6 +162,42 @@ def rib_window_attn_bwd(p, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q,
                                     workspace, workspace_bytes, stream)
     if st != RIB_OK:
         raise RibError(st, "rib_window_attn_bwd")
+
+
+def rib_window_attn_gated_fwd_status(p, q, k, v, f_q, f_k, gate, out_gated, out_raw, lse, stream=None) -> int:
+    return load().rib_window_attn_gated_fwd(ctypes.byref(p) if p is not None else None, _ptr(q), _ptr(k), _ptr(v),
+                                            _ptr(f_q), _ptr(f_k), _ptr(gate), _ptr(out_gated), _ptr(out_raw),
+                                            _ptr(lse), _stream(stream) if stream != 0 else 0)
+
+
+def rib_window_attn_gated_fwd(p, q, k, v, f_q, f_k, gate, out_gated, out_raw=None, lse=None, stream=None) -> None:
+    st = rib_window_attn_gated_fwd_status(p, q, k, v, f_q, f_k, gate, out_gated, out_raw, lse, stream)
+    if st != RIB_OK:
+        raise RibError(st, "rib_window_attn_gated_fwd")
+
+
+def rib_window_attn_gated_bwd_workspace_bytes(p) -> int:
+    return int(load().rib_window_attn_gated_bwd_workspace_bytes(ctypes.byref(p) if p is not None else None))
+
+
+def rib_window_attn_gated_bwd_status(p, q, k, v, f_q, f_k, gate, out_raw, d_out_gated, lse, dq, dk, dv, dgate,
+                                     df_q, df_k, workspace, workspace_bytes=None, stream=None) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = 0 if workspace is None or isinstance(workspace, int) else \
+            workspace.numel() * workspace.element_size()
+    return load().rib_window_attn_gated_bwd(ctypes.byref(p) if p is not None else None, _ptr(q), _ptr(k), _ptr(v),
+                                            _ptr(f_q), _ptr(f_k), _ptr(gate), _ptr(out_raw), _ptr(d_out_gated),
+                                            _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dgate), _ptr(df_q),
+                                            _ptr(df_k), _ptr(workspace), int(workspace_bytes),
+                                            _stream(stream) if stream != 0 else 0)
+
+
+def rib_window_attn_gated_bwd(p, q, k, v, f_q, f_k, gate, out_raw, d_out_gated, lse, dq, dk, dv, dgate, df_q, df_k,
+                              workspace, workspace_bytes=None, stream=None) -> None:
+    st = rib_window_attn_gated_bwd_status(p, q, k, v, f_q, f_k, gate, out_raw, d_out_gated, lse, dq, dk, dv, dgate,
+                                          df_q, df_k, workspace, workspace_bytes, stream)
+    if st != RIB_OK:
+        raise RibError(st, "rib_window_attn_gated_bwd")
 
 
 def make_gen_params(window, heads, r, L=10, d_h=32, dtype="f32") -> RibGenParams:

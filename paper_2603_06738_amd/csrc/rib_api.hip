@@ -31,6 +31,8 @@ rib_status make_geo(const rib_params *p, Geo *g)
     g->tstride = p->token_stride != 0 ? p->token_stride : C;
     g->scale_c = p->scale_c; g->scale_p = p->scale_p;
     g->units = (int64_t)p->B * g->nwx * g->nwy * p->heads;
+    g->gate = nullptr;
+    g->out_raw = nullptr;
     g->inv_m = p->window > 1 ? (uint32_t)((((uint64_t)1 << 32) + p->window - 1) / p->window) : 0xffffffffu;
     // every kernel indexes workgroups with 32-bit block ids and tokens with int
     const int64_t blocks = g->units * ((g->N + 63) / 64);
@@ -84,6 +86,60 @@ rib_status rib_window_attn_fwd(const rib_params *p, const void *q, const void *k
                             (hipStream_t)stream);
     else
         e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out, lse, (hipStream_t)stream);
+    return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
+}
+
+rib_status rib_window_attn_gated_fwd(const rib_params *p, const void *q, const void *k, const void *v, const void *f_q,
+                                     const void *f_k, const void *gate, void *out_gated, void *out_raw, float *lse,
+                                     void *stream)
+{
+    Geo g;
+    rib_status st = make_geo(p, &g);
+    if (st != RIB_OK) return st;
+    if (!q || !k || !v || !gate || !out_gated) return RIB_ERR_NULL;
+    if (g.r > 0 && (!f_q || !f_k)) return RIB_ERR_NULL;
+    g.gate = gate;
+    g.out_raw = out_raw;
+    hipError_t e;
+    if (mfma_fwd_supported(g, p->dtype))
+        e = launch_mfma_fwd(g, (p->flags & RIB_FLAG_FORCE_ROW_MAX) != 0, q, k, v, f_q, f_k, out_gated, lse,
+                            (hipStream_t)stream);
+    else
+        e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out_gated, lse, (hipStream_t)stream);
+    return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
+}
+
+size_t rib_window_attn_gated_bwd_workspace_bytes(const rib_params *p)
+{
+    Geo g;
+    if (make_geo(p, &g) != RIB_OK) return 0;
+    return valu_bwd_workspace(g) + gated_dout_bytes(g, p->dtype);
+}
+
+rib_status rib_window_attn_gated_bwd(const rib_params *p, const void *q, const void *k, const void *v, const void *f_q,
+                                     const void *f_k, const void *gate, const void *out_raw, const void *d_out_gated,
+                                     const float *lse, void *dq, void *dk, void *dv, void *dgate, float *df_q,
+                                     float *df_k, void *workspace, size_t workspace_bytes, void *stream)
+{
+    Geo g;
+    rib_status st = make_geo(p, &g);
+    if (st != RIB_OK) return st;
+    if (!q || !k || !v || !gate || !out_raw || !d_out_gated || !lse || !dq || !dk || !dv || !dgate) return RIB_ERR_NULL;
+    if (g.r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
+    const size_t base = valu_bwd_workspace(g);
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < base + gated_dout_bytes(g, p->dtype))
+        return RIB_ERR_WORKSPACE;
+    // dO = dO' * gate lives behind the plain backward's scratch; the delta pass writes it (and dgate),
+    // the main kernels then run exactly as for the plain operator.
+    void *d_out = (char *)workspace + base;
+    g.gate = gate;
+    hipError_t e;
+    if (mfma_bwd_supported(g, p->dtype))
+        e = launch_mfma_bwd(g, q, k, v, f_q, f_k, out_raw, d_out_gated, lse, dq, dk, dv, df_q, df_k, workspace,
+                            (hipStream_t)stream, d_out, dgate);
+    else
+        e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out_raw, d_out_gated, lse, dq, dk, dv, df_q, df_k, workspace,
+                            (hipStream_t)stream, d_out, dgate);
     return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
 }
 

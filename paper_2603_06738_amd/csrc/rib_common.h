@@ -19,6 +19,11 @@ struct Geo {
     float scale_c, scale_p;
     int64_t units;    // B*nwy*nwx*heads (window, head) pairs
     uint32_t inv_m;   // ceil(2^32 / M): n / M == mulhi(n, inv_m) for every n < 2^24 (M >= 2)
+    // Gated epilogue (CLA, paper Eq. 9), forward only: when `gate` is set the kernels store
+    // O * gate to their output and, if `out_raw` is set too, the ungated O there (both dense
+    // [B][H][W][C] in the problem's storage type).  Null for the plain operator.
+    const void *gate;
+    void *out_raw;
 };
 
 using bf16_t = uint16_t;  // raw bf16 storage
@@ -136,7 +141,7 @@ hipError_t launch_valu_fwd(const Geo &g, int dtype, const void *q, const void *k
 hipError_t launch_valu_bwd(const Geo &g, int dtype, const void *q, const void *k, const void *v,
                            const void *fq, const void *fk, const void *out, const void *dout,
                            const float *lse, void *dq, void *dk, void *dv, float *dfq, float *dfk,
-                           void *ws, hipStream_t st);
+                           void *ws, hipStream_t st, void *gated_dout = nullptr, void *dgate = nullptr);
 size_t valu_bwd_workspace(const Geo &g);
 
 // Backward scratch layout (both kernel families): delta [units][N] fp32, then the
@@ -145,6 +150,11 @@ struct BwdWs {
     size_t delta_off, dfq_off, dfk_off, total;
 };
 BwdWs bwd_ws_layout(const Geo &g);
+// Gated backward: the same scratch followed by one grid tensor for dO = dO' * gate.
+size_t gated_dout_bytes(const Geo &g, int dtype);
+// delta, dO = dO' * gate (into `dout`, storage type) and dgate = dO' * O in one pass.
+hipError_t launch_delta_gated(const Geo &g, int dtype, const void *out_raw, const void *dout_gated, const void *gate,
+                              float *delta, void *dout, void *dgate, hipStream_t st);
 // delta[u][i] = dO[i].O[i] per head (dtype = RIB_F32 / RIB_BF16 storage of out, dout).
 hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *dout, float *delta, hipStream_t st);
 // dF[hd][e] = sum over windows (ascending) of part[(w*heads + hd)][e].
@@ -159,6 +169,9 @@ hipError_t launch_mfma_fwd(const Geo &g, int force_max, const void *q, const voi
 bool mfma_bwd_supported(const Geo &g, int dtype);
 hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq,
                            const void *fk, const void *out, const void *dout, const float *lse, void *dq,
-                           void *dk, void *dv, float *dfq, float *dfk, void *ws, hipStream_t st);
+                           void *dk, void *dv, float *dfq, float *dfk, void *ws, hipStream_t st,
+                           void *gated_dout = nullptr, void *dgate = nullptr);
+// With g.gate set, `dout` is the gradient of the GATED output: the launchers above first run
+// launch_delta_gated (delta, dO into gated_dout, dgate) and feed gated_dout to the main kernels.
 
 }  // namespace rib

@@ -1117,7 +1117,7 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     float *delta = (float *)((char *)ws + l.delta_off);
     float *pq = (float *)((char *)ws + l.dfq_off);
     float *pk = (float *)((char *)ws + l.dfk_off);
-    hipError_t e = launch_delta(g, RIB_BF16, out, dout, delta, st);
+    hipError_t e = g.gate ? hipSuccess : launch_delta(g, RIB_BF16, out, dout, delta, st);   // (gated: done by the caller)
     if (e != hipSuccess) return e;
 
     if (bwd_fast_ok(g)) {
@@ -1179,8 +1179,14 @@ bool mfma_bwd_supported(const Geo &g, int dtype)
 
 hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
                            const void *out, const void *dout, const float *lse, void *dq, void *dk, void *dv,
-                           float *dfq, float *dfk, void *ws, hipStream_t st)
+                           float *dfq, float *dfk, void *ws, hipStream_t st, void *gated_dout, void *dgate)
 {
+    if (g.gate) {
+        float *delta = (float *)((char *)ws + bwd_ws_layout(g).delta_off);
+        hipError_t e = launch_delta_gated(g, RIB_BF16, out, dout, g.gate, delta, gated_dout, dgate, st);
+        if (e != hipSuccess) return e;
+        dout = gated_dout;
+    }
     if (bwd_fast_ok(g) && !columns_are_free(g)) {
         if (g.d + g.r <= 48) return launch<48, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
         return launch<64, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);

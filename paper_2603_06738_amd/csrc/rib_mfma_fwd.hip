@@ -666,11 +666,20 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
         const int n = q0 + qb * 32 + col;
         if (n >= g.N) continue;
         const float inv = 1.f / l;
-        bf16_t *dst = out + (int64_t)tok[n] * g.C + hd * g.d;
+        const int64_t obase = (int64_t)tok[n] * g.C + hd * g.d;
+        bf16_t *dst = out + obase;
 #pragma unroll
         for (int i = 0; i < 16; i += 2) {
             int dv = 8 * (i >> 2) + 4 * hf + (i & 3);
-            if (dv < g.d) *(uint32_t *)(dst + dv) = pack_bf16(O[qb][i] * inv, O[qb][i + 1] * inv);
+            if (dv >= g.d) continue;
+            const float o0 = O[qb][i] * inv, o1 = O[qb][i + 1] * inv;
+            if (g.gate == nullptr) {
+                *(uint32_t *)(dst + dv) = pack_bf16(o0, o1);
+            } else {    // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
+                const uint32_t gw = *(const uint32_t *)((const bf16_t *)g.gate + obase + dv);
+                *(uint32_t *)(dst + dv) = pack_bf16(o0 * lo_bf16(gw), o1 * hi_bf16(gw));
+                if (g.out_raw) *(uint32_t *)((bf16_t *)g.out_raw + obase + dv) = pack_bf16(o0, o1);
+            }
         }
         if (lse != nullptr && hf == 0) lse[u * g.N + n] = (mrun[qb] + __builtin_amdgcn_logf(l)) * kLn2;
     }
@@ -812,7 +821,14 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
             for (int p = 0; p < 16; ++p) {
                 const int row = p * 4 + sub;
                 const uint32_t w2 = *(const uint32_t *)(Os + row * ORS + 2 * j);
-                *(uint32_t *)(out + (int64_t)tok[q0 + row] * g.C + hd * g.d + 2 * j) = w2;
+                const int64_t off = (int64_t)tok[q0 + row] * g.C + hd * g.d + 2 * j;
+                if (g.gate == nullptr) {
+                    *(uint32_t *)(out + off) = w2;
+                } else {    // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
+                    const uint32_t gw = *(const uint32_t *)((const bf16_t *)g.gate + off);
+                    *(uint32_t *)(out + off) = pack_bf16(lo_bf16(w2) * lo_bf16(gw), hi_bf16(w2) * hi_bf16(gw));
+                    if (g.out_raw) *(uint32_t *)((bf16_t *)g.out_raw + off) = w2;
+                }
             }
         }
     }

@@ -146,9 +146,20 @@ __global__ __launch_bounds__(kThreads) void valu_fwd_kernel(Geo g, int nblk, con
     if (!live) return;
     const float inv = 1.f / l;
     T *dst = out + tq * g.C + hd * g.d;
+    if (g.gate == nullptr) {
 #pragma unroll
-    for (int t = 0; t < DV; ++t)
-        if (t % kSplit == part && t < g.d) store_as(dst + t, o[t] * inv);
+        for (int t = 0; t < DV; ++t)
+            if (t % kSplit == part && t < g.d) store_as(dst + t, o[t] * inv);
+    } else {    // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
+        const T *gt = (const T *)g.gate + tq * g.C + hd * g.d;
+        T *raw = g.out_raw ? (T *)g.out_raw + tq * g.C + hd * g.d : nullptr;
+#pragma unroll
+        for (int t = 0; t < DV; ++t)
+            if (t % kSplit == part && t < g.d) {
+                store_as(dst + t, o[t] * inv * widen(gt[t]));
+                if (raw) store_as(raw + t, o[t] * inv);
+            }
+    }
     if (lse != nullptr && part == 0) lse[u * g.N + i] = (m + log2f(l)) * kLn2;
 }
 
@@ -210,6 +221,46 @@ __global__ __launch_bounds__(kThreads) void valu_delta_kernel(Geo g, int nchunk,
         for (int off = 8; off >= 1; off >>= 1) acc[it] += __shfl_xor(acc[it], off);
         const int nl = it * 16 + grp;
         if (sub == 0 && n0 + nl < g.N) delta[u * g.N + n0 + nl] = acc[it];
+    }
+}
+
+// Gated variant (CLA, Eq. 9: O' = O * G): from the gradient dO' of the gated output,
+//   dO = dO' * G (rounded to the storage type, written for the main kernels),
+//   dG = dO' * O,      delta = dO . O   (with the rounded dO, as the main kernels see it).
+// Same mapping of lanes to (token, head) slices as above, so every element of the grid is
+// written exactly once.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void valu_delta_gated_kernel(Geo g, int nchunk, const T *__restrict__ out,
+                                                                    const T *__restrict__ dout_g, const T *__restrict__ gate,
+                                                                    float *__restrict__ delta, T *__restrict__ dout,
+                                                                    T *__restrict__ dgate)
+{
+    __shared__ int64_t tok[64];
+    const int64_t u = blockIdx.x / nchunk;
+    const int n0 = (int)(blockIdx.x - u * nchunk) * 64;
+    const int w = (int)(u / g.heads), hd = (int)(u - (int64_t)w * g.heads);
+    const int tid = threadIdx.x, grp = tid >> 4, sub = tid & 15;
+    if (tid < 64) tok[tid] = n0 + tid < g.N ? grid_token(g, w, n0 + tid) : -1;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int64_t t = tok[it * 16 + grp];
+        float acc = 0.f;
+        if (t >= 0) {
+            const int64_t base = t * g.C + hd * g.d;
+            for (int c = sub; c < g.d; c += 16) {
+                const float o = widen(out[base + c]), gp = widen(dout_g[base + c]), gv = widen(gate[base + c]);
+                T d_o;
+                store_as(&d_o, gp * gv);
+                dout[base + c] = d_o;
+                store_as(dgate + base + c, gp * o);
+                acc = fmaf(widen(d_o), o, acc);
+            }
+        }
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+        const int nl = it * 16 + grp;
+        if (sub == 0 && n0 + nl < g.N) delta[u * g.N + n0 + nl] = acc;
     }
 }
 
@@ -407,7 +458,7 @@ hipError_t bwd_t(const Geo &g, const void *q, const void *k, const void *v, cons
     float *pk = (float *)((char *)ws + l.dfk_off);
     int64_t rows = g.units * g.N;
     (void)rows;
-    hipError_t e = launch_delta(g, sizeof(T) == 2 ? RIB_BF16 : RIB_F32, out, dout, delta, st);
+    hipError_t e = g.gate ? hipSuccess : launch_delta(g, sizeof(T) == 2 ? RIB_BF16 : RIB_F32, out, dout, delta, st);
     if (e != hipSuccess) return e;
     int nblk = (g.N + kRows - 1) / kRows;
     dim3 grid((unsigned)(g.units * nblk));
@@ -462,6 +513,28 @@ hipError_t launch_delta(const Geo &g, int dtype, const void *out, const void *do
     return hipGetLastError();
 }
 
+size_t gated_dout_bytes(const Geo &g, int dtype)
+{
+    const size_t n = (size_t)g.B * g.H * g.W * g.C * (dtype == RIB_BF16 ? 2 : 4);
+    return (n + 255) / 256 * 256;
+}
+
+hipError_t launch_delta_gated(const Geo &g, int dtype, const void *out_raw, const void *dout_gated, const void *gate,
+                              float *delta, void *dout, void *dgate, hipStream_t st)
+{
+    const int nchunk = (g.N + 63) / 64;
+    dim3 grid((unsigned)(g.units * nchunk));
+    if (dtype == RIB_BF16)
+        hipLaunchKernelGGL((valu_delta_gated_kernel<bf16_t>), grid, dim3(kThreads), 0, st, g, nchunk,
+                           (const bf16_t *)out_raw, (const bf16_t *)dout_gated, (const bf16_t *)gate, delta,
+                           (bf16_t *)dout, (bf16_t *)dgate);
+    else
+        hipLaunchKernelGGL((valu_delta_gated_kernel<float>), grid, dim3(kThreads), 0, st, g, nchunk,
+                           (const float *)out_raw, (const float *)dout_gated, (const float *)gate, delta,
+                           (float *)dout, (float *)dgate);
+    return hipGetLastError();
+}
+
 hipError_t launch_reduce_df(const Geo &g, const float *part_q, const float *part_k, float *dfq, float *dfk,
                             hipStream_t st)
 {
@@ -492,8 +565,14 @@ hipError_t launch_valu_fwd(const Geo &g, int dtype, const void *q, const void *k
 
 hipError_t launch_valu_bwd(const Geo &g, int dtype, const void *q, const void *k, const void *v, const void *fq,
                            const void *fk, const void *out, const void *dout, const float *lse, void *dq, void *dk,
-                           void *dv, float *dfq, float *dfk, void *ws, hipStream_t st)
+                           void *dv, float *dfq, float *dfk, void *ws, hipStream_t st, void *gated_dout, void *dgate)
 {
+    if (g.gate) {
+        float *delta = (float *)((char *)ws + bwd_ws_layout(g).delta_off);
+        hipError_t e = launch_delta_gated(g, dtype, out, dout, g.gate, delta, gated_dout, dgate, st);
+        if (e != hipSuccess) return e;
+        dout = gated_dout;
+    }
     RIB_VALU_DISPATCH(bwd_t, g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st)
 }
 

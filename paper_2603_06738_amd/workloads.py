@@ -198,3 +198,12 @@ def make_feature_grads(heads: int, M: int, r: int, seed: int = _SEED0 + 901) -> 
     rng = np.random.Generator(np.random.Philox(key=seed))
     shape = (heads, M * M, r)
     return {"df_q": rng.standard_normal(shape, dtype=np.float32), "df_k": rng.standard_normal(shape, dtype=np.float32)}
+
+
+def make_gate(wl: Workload, seed_offset: int = 0x4000) -> np.ndarray:
+    """A synthetic CLA gate G [B,H,W,C] (paper Eq. 8-9): uniform in (0, 1), the range of the
+    sigmoid that produces it; rounded to bf16 for bf16 workloads.  Its own Philox stream, so the
+    other tensors of the workload do not change."""
+    rng = np.random.Generator(np.random.Philox(key=wl.seed + seed_offset))
+    g = rng.random((wl.B, wl.H, wl.W, wl.C), dtype=np.float32)
+    return round_to_bf16(g) if wl.dtype == "bf16" else g

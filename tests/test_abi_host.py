@@ -126,3 +126,28 @@ def test_generator_params_layout_and_validation():
         a = list(b)
         a[i] = None
         assert rb.rib_features_bwd_status(ok, *a, 0x1000, need, stream=0) == 1
+
+
+def test_gated_entry_points_validate():
+    p = good()
+    ptrs = dict(q=FAKE, k=FAKE, v=FAKE, f_q=FAKE, f_k=FAKE, gate=FAKE, out_gated=FAKE, out_raw=None, lse=None)
+
+    def fwd(**kw):
+        a = dict(ptrs)
+        a.update(kw)
+        return rb.rib_window_attn_gated_fwd_status(p, *[a[n] for n in ("q", "k", "v", "f_q", "f_k", "gate", "out_gated",
+                                                                        "out_raw", "lse")], stream=0)
+
+    assert fwd(gate=None) == 1 and fwd(out_gated=None) == 1 and fwd(q=None) == 1
+    assert rb.rib_window_attn_gated_fwd_status(good(H=10), *([FAKE] * 9), stream=0) == 2
+    need = rb.rib_window_attn_gated_bwd_workspace_bytes(p)
+    plain = rb.rib_window_attn_bwd_workspace_bytes(p)
+    assert need % 256 == 0 and need >= plain + 2 * 8 * 8 * 8 * 4
+    b = [FAKE] * 15
+    assert rb.rib_window_attn_gated_bwd_status(p, *b, 0x1000, need - 1, stream=0) == 5
+    assert rb.rib_window_attn_gated_bwd_status(p, *b, 0x1010, need, stream=0) == 5
+    for i in range(15):
+        a = list(b)
+        a[i] = None
+        assert rb.rib_window_attn_gated_bwd_status(p, *a, 0x1000, need, stream=0) == 1, i
+    assert rb.rib_window_attn_gated_bwd_workspace_bytes(good(shift=9)) == 0

@@ -191,3 +191,52 @@ def test_paper_schedule_layers(oracle, gh, name):
     ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
     for nm, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
         assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], nm
+
+
+GATED = [
+    wk.custom("gate-f32", "f32", 1, 16, 16, 2, 30, 16, 16, 3, 231, backward=True),          # vector-ALU kernels
+    wk.custom("gate-m12", "bf16", 1, 24, 12, 2, 30, 16, 12, 7, 232, backward=True),         # general matrix-core kernels
+    wk.custom("gate-m32", "bf16", 2, 32, 64, 3, 30, 18, 32, 16, 233, backward=True),        # fast kernels
+    wk.custom("gate-d32", "bf16", 1, 16, 32, 2, 32, 32, 16, 0, 234, backward=True),
+]
+
+
+@pytest.mark.parametrize("wl", GATED, ids=lambda w: w.name)
+def test_gated_forward_and_backward(oracle, gh, wl):
+    """CLA gate (Eq. 9) fused into the epilogue, and the gated backward (dO = dO' * G and
+    dG = dO' * O formed in the delta pass).  Bounds: the north-star tolerance for every tensor;
+    for dG the forward's error in O is multiplied by dO', hence tol * max(1, max|dO'|)."""
+    import torch
+    x = wk.make_inputs(wl)
+    gate = wk.make_gate(wl)
+    g = geometry(oracle, wl)
+    Og_ref, O_ref, lse_ref = oracle.gated_fwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], gate)
+    ref = oracle.gated_bwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], gate, x["d_out"])
+    t = gh.device_inputs(wl, x)
+    tg = rb.to_device(gate, wl.dtype, gh.DEV)
+    p = rb.params_of(wl)
+    td = gh.tdtype(wl)
+    grid = (wl.B, wl.H, wl.W, wl.C)
+    nan = float("nan")
+    out_g, out_raw = (torch.full(grid, nan, dtype=td, device=gh.DEV) for _ in range(2))
+    lse = torch.full((wl.n_windows, wl.heads, wl.N), nan, dtype=torch.float32, device=gh.DEV)
+    rb.rib_window_attn_gated_fwd(p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], tg, out_g, out_raw, lse)
+    torch.cuda.synchronize()
+    tol = gh.TOL[wl.dtype]
+    assert gh.max_abs(gh.host(out_g), Og_ref) <= tol
+    assert gh.max_abs(gh.host(out_raw), O_ref) <= tol
+    assert gh.max_abs(gh.host(lse), lse_ref) <= tol
+    # inference form: no raw output
+    out_g2 = torch.full(grid, nan, dtype=td, device=gh.DEV)
+    rb.rib_window_attn_gated_fwd(p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], tg, out_g2, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out_g, out_g2)
+    dq, dk, dv, dgate = (torch.full(grid, nan, dtype=td, device=gh.DEV) for _ in range(4))
+    dfq, dfk = (torch.full((wl.heads, wl.N, wl.r), nan, dtype=torch.float32, device=gh.DEV) for _ in range(2))
+    ws = torch.empty(rb.rib_window_attn_gated_bwd_workspace_bytes(p), dtype=torch.uint8, device=gh.DEV)
+    rb.rib_window_attn_gated_bwd(p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], tg, out_raw, t["d_out"], lse,
+                                 dq, dk, dv, dgate, dfq, dfk, ws)
+    torch.cuda.synchronize()
+    for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), (dq, dk, dv, dfq, dfk), ref):
+        assert gh.max_abs(gh.host(a), b) <= tol, name
+    assert gh.max_abs(gh.host(dgate), ref[5]) <= tol * max(1.0, float(np.abs(x["d_out"]).max())), "dG"

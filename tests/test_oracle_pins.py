@@ -298,3 +298,49 @@ def test_bf16_input_rounding_is_shared_not_hidden(oracle):
         assert np.all(np.abs(x[n] - raw[n]) <= np.abs(raw[n]) * 2.0 ** -8)
     import torch
     np.testing.assert_array_equal(torch.tensor(raw["q"]).bfloat16().float().numpy(), x["q"])
+
+
+def test_gate_of_ones_is_the_plain_operator(oracle):
+    wl = wk.custom("gate1", "f32", 1, 4, 8, 2, 3, 2, 4, 1, 121, backward=True)
+    x = wk.make_inputs(wl)
+    g = geometry(oracle, wl)
+    ones = np.ones((wl.B, wl.H, wl.W, wl.C), np.float32)
+    Og, O, lse = oracle.gated_fwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], ones)
+    O_ref, lse_ref = oracle.fwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"])
+    np.testing.assert_array_equal(Og, O_ref)
+    np.testing.assert_array_equal(O, O_ref)
+    np.testing.assert_array_equal(lse, lse_ref)
+    got = oracle.gated_bwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], ones, x["d_out"])
+    ref = _run_bwd(oracle, wl, x, x["d_out"])
+    for a, b in zip(got[:5], ref):
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(got[5], x["d_out"].astype(np.float64) * O_ref, rtol=0, atol=1e-14)
+
+
+def test_gated_backward_by_finite_differences(oracle):
+    """Eq. 9 (O' = O * G) chained behind the brute-force forward: central
+    differences of sum(O' * R) in the gate itself and in q, k, v, f_q, f_k."""
+    wl = wk.custom("gatefd", "f32", 1, 4, 4, 2, 2, 2, 2, 1, 131, scale_c=0.7, scale_p=0.8, backward=True)
+    x = wk.make_inputs(wl)
+    gate = wk.make_gate(wl).astype(np.float64)
+    R = x["d_out"].astype(np.float64)
+    g = geometry(oracle, wl)
+    got = oracle.gated_bwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], gate, x["d_out"])
+    grads = dict(zip(("q", "k", "v", "f_q", "f_k", "gate"), got))
+    base = {n: a.astype(np.float64) for n, a in x.items()}
+    base["gate"] = gate
+    rng = np.random.default_rng(9)
+    eps = 1e-3
+
+    def loss(z):
+        return float((brute_force_fwd(wl, z) * z["gate"] * R).sum())
+
+    for name, gr in grads.items():
+        for fi in rng.choice(base[name].size, size=min(8, base[name].size), replace=False):
+            idx = np.unravel_index(fi, base[name].shape)
+            zp = {n: a.copy() for n, a in base.items()}
+            zm = {n: a.copy() for n, a in base.items()}
+            zp[name][idx] += eps
+            zm[name][idx] -= eps
+            fd = (loss(zp) - loss(zm)) / (2 * eps)
+            assert abs(fd - gr[idx]) < 5e-6 * max(1.0, abs(fd)), (name, idx, fd, gr[idx])

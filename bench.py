@@ -144,8 +144,11 @@ def time_gated(rb, torch, wl, reps=30):
         rb.rib_window_attn_gated_bwd(r.p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], gate, r.out, t["d_out"], r.lse,
                                      r.dq, r.dk, r.dv, dgate, r.dfq, r.dfk, ws)
 
+    def fwd_infer():
+        rb.rib_window_attn_gated_fwd(r.p, t["q"], t["k"], t["v"], t["f_q"], t["f_k"], gate, out_g, None, None)
+
     res = {}
-    for name, fn in (("fwd_ms", fwd), ("bwd_ms", bwd)):
+    for name, fn in (("fwd_ms", fwd), ("fwd_inference_ms", fwd_infer), ("bwd_ms", bwd)):
         for _ in range(5):
             fn()
         torch.cuda.synchronize()

@@ -798,6 +798,15 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     // private LDS area ([64 tokens][34 bf16]: the odd dword stride keeps both sides
     // conflict-free) and writes it out with 16 lanes per token.
     constexpr int ORS = 34;
+    // (gated epilogue: the gate words of the rows this lane will store are requested now, so
+    // that their latency hides behind the normalisation and the transpose)
+    const int sub = lane >> 4, j = lane & 15, jc = 2 * j < g.d ? j : 0;
+    uint32_t gw[16];
+    if (g.gate != nullptr) {
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+            gw[p] = *(const uint32_t *)((const bf16_t *)g.gate + (int64_t)tok[q0 + p * 4 + sub] * g.C + hd * g.d + 2 * jc);
+    }
     __syncthreads();                                   // every wave is done with the K/V tiles
     bf16_t *Os = tiles + wave * 64 * ORS;
 #pragma unroll
@@ -814,21 +823,17 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
             lse[u * g.N + n] = (mrun[qb] + __builtin_amdgcn_logf(l) + (redo ? 0.f : kTruncLog2)) * kLn2;
     }
     __syncthreads();
-    {
-        const int sub = lane >> 4, j = lane & 15;
-        if (2 * j < g.d) {
+    if (2 * j < g.d) {
 #pragma unroll
-            for (int p = 0; p < 16; ++p) {
-                const int row = p * 4 + sub;
-                const uint32_t w2 = *(const uint32_t *)(Os + row * ORS + 2 * j);
-                const int64_t off = (int64_t)tok[q0 + row] * g.C + hd * g.d + 2 * j;
-                if (g.gate == nullptr) {
-                    *(uint32_t *)(out + off) = w2;
-                } else {    // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
-                    const uint32_t gw = *(const uint32_t *)((const bf16_t *)g.gate + off);
-                    *(uint32_t *)(out + off) = pack_bf16(lo_bf16(w2) * lo_bf16(gw), hi_bf16(w2) * hi_bf16(gw));
-                    if (g.out_raw) *(uint32_t *)((bf16_t *)g.out_raw + off) = w2;
-                }
+        for (int p = 0; p < 16; ++p) {
+            const int row = p * 4 + sub;
+            const uint32_t w2 = *(const uint32_t *)(Os + row * ORS + 2 * j);
+            const int64_t off = (int64_t)tok[q0 + row] * g.C + hd * g.d + 2 * j;
+            if (g.gate == nullptr) {
+                *(uint32_t *)(out + off) = w2;
+            } else {    // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
+                *(uint32_t *)(out + off) = pack_bf16(lo_bf16(w2) * lo_bf16(gw[p]), hi_bf16(w2) * hi_bf16(gw[p]));
+                if (g.out_raw) *(uint32_t *)((bf16_t *)g.out_raw + off) = w2;
             }
         }
     }

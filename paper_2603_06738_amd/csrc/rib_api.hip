@@ -33,6 +33,7 @@ rib_status make_geo(const rib_params *p, Geo *g)
     g->units = (int64_t)p->B * g->nwx * g->nwy * p->heads;
     g->gate = nullptr;
     g->out_raw = nullptr;
+    g->flags = p->flags;
     g->inv_m = p->window > 1 ? (uint32_t)((((uint64_t)1 << 32) + p->window - 1) / p->window) : 0xffffffffu;
     // every kernel indexes workgroups with 32-bit block ids and tokens with int
     const int64_t blocks = g->units * ((g->N + 63) / 64);

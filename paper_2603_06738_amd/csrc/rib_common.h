@@ -24,6 +24,7 @@ struct Geo {
     // [B][H][W][C] in the problem's storage type).  Null for the plain operator.
     const void *gate;
     void *out_raw;
+    int flags;        // rib_params.flags
 };
 
 using bf16_t = uint16_t;  // raw bf16 storage

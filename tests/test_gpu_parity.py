@@ -258,3 +258,25 @@ def test_run_to_run_identical(gh, name):
         runs.append((out, lse, *gh.gpu_bwd(wl, t, out, lse)))
     for a, b in zip(*runs):
         assert torch.equal(a, b)
+
+
+WIDE = [
+    wk.custom("wide-d30r16", "bf16", 1, 32, 64, 2, 30, 16, 32, 16, 241, backward=True),     # extras in spare columns
+    wk.custom("wide-d30r18", "bf16", 1, 32, 32, 2, 30, 18, 32, 0, 242, backward=True),      # extras in the C operand, 48 columns
+    wk.custom("wide-d30r34", "bf16", 1, 32, 32, 2, 30, 34, 32, 5, 243, backward=True),      # ... 64 columns
+    wk.custom("wide-d32r32", "bf16", 1, 32, 32, 2, 32, 32, 32, 0, 244, backward=True),
+    wk.custom("wide-d30r24", "bf16", 1, 32, 32, 2, 30, 24, 32, 0, 245, backward=True),      # 64 columns, extras in spare columns
+]
+
+
+@pytest.mark.parametrize("wl", WIDE, ids=lambda w: w.name)
+def test_backward_wide_workgroups(oracle, gh, wl):
+    """The 8-wave backward kernels (default only for large windows) forced onto small problems so
+    that every variant is checked element by element; they must also agree with the 4-wave kernels
+    to within the tolerance."""
+    x = wk.make_inputs(wl)
+    t, out, lse = _check_fwd(oracle, gh, wl, x)
+    got = gh.gpu_bwd(wl, t, out, lse, flags=rb.RIB_FLAG_BWD_WIDE)
+    ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+        assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name

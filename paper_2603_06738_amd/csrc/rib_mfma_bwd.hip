@@ -1194,10 +1194,12 @@ hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const voi
         dout = gated_dout;
     }
     if (bwd_fast_ok(g) && !columns_are_free(g)) {
-        if (g.d + g.r <= 48) return launch<48, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
+        // (the 48-column staging code serves RIB rows of up to 32 values)
+        if (g.d + g.r <= 48 && g.r <= 32)
+            return launch<48, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
         return launch<64, 32, true>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
     }
-    const bool small_qk = g.d + g.r + 2 <= 48, small_v = g.d + 2 <= 32;
+    const bool small_qk = g.d + g.r + 2 <= 48 && g.r <= 32, small_v = g.d + 2 <= 32;
     if (small_qk && small_v) return launch<48, 32>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
     if (small_v) return launch<64, 32>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);
     return launch<64, 48>(g, q, k, v, fq, fk, out, dout, lse, dq, dk, dv, dfq, dfk, ws, st);

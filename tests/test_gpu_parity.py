@@ -280,3 +280,32 @@ def test_backward_wide_workgroups(oracle, gh, wl):
     ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
     for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
         assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name
+
+
+def _corner_cases():
+    c = wk.custom
+    combos = [  # (d, r, M, shift): corners of what the matrix-core kernels accept and just outside
+        (32, 0, 8, 3), (32, 2, 16, 0), (2, 2, 16, 1), (4, 4, 16, 0), (2, 62, 16, 0), (16, 48, 16, 5),
+        (8, 40, 16, 0), (28, 36, 16, 2), (30, 32, 16, 0), (6, 34, 16, 0), (32, 30, 16, 7), (20, 44, 16, 0),
+        (30, 16, 48, 9), (18, 18, 32, 0), (64, 0, 8, 0), (34, 16, 16, 0), (31, 16, 16, 0), (30, 17, 16, 0),
+    ]
+    out = []
+    for i, (d, r, M, s) in enumerate(combos):
+        B, H, W = (1, M, 2 * M) if M < 48 else (1, M, M)
+        out.append(c(f"corner-d{d}r{r}m{M}", "bf16", B, H, W, 2, d, r, M, s, 300 + i, backward=True))
+    return out
+
+
+@pytest.mark.parametrize("wl", _corner_cases(), ids=lambda w: w.name)
+def test_corner_shapes(oracle, gh, wl):
+    """Head dims and ranks at the edges of each kernel family's range (and one step outside,
+    where the library must fall back to another family on its own): forward in both softmax
+    paths and backward, every element."""
+    x = wk.make_inputs(wl)
+    _check_fwd(oracle, gh, wl, x, flags=FORCE_MAX)
+    t, out, lse = _check_fwd(oracle, gh, wl, x)
+    got = gh.gpu_bwd(wl, t, out, lse)
+    ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    names = ("dQ", "dK", "dV", "dF_q", "dF_k") if wl.r > 0 else ("dQ", "dK", "dV")
+    for name, a, b in zip(names, got, ref):
+        assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name

@@ -28,6 +28,8 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
 # plain copy of known size (profiles/c5_step_hbm_traffic.md); only for the workload it was measured on.
 MEASURED_FWD_TRAFFIC = {"c5": 230.6e6}
+# the same for the backward's launches (delta 109.7 + dkv 449.5 + dq 370.2 + reduce 114.1 MB)
+MEASURED_BWD_TRAFFIC = {"c5": 1043.5e6}
 
 
 def parse():
@@ -237,7 +239,7 @@ def main():
         res["roofline_bwd"] = {"kernel": "backward (" + rb.kernel_name(r.p, True) + ", all its launches)",
                                "bound": "mfma" if bmfma else "alu", "achieved": round(bwd_tflops, 2),
                                "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4),
-                               "traffic": None}
+                               "traffic": MEASURED_BWD_TRAFFIC.get(wl.name), "algorithmic_flop": wl.bwd_flop}
     del r
     torch.cuda.empty_cache()
 

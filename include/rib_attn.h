@@ -79,13 +79,12 @@ enum {
      * tracking only if a row fails.  Results are the same within rounding; this
      * exists so that both code paths can be tested and timed. */
     RIB_FLAG_FORCE_ROW_MAX = 1,
-    /* Backward: use the wide workgroups (8 waves sharing each streamed tile)
-     * whenever the window has a multiple of 512 tokens.  By default they are
-     * chosen only for windows of 4096 tokens or more with enough work to fill
-     * the chip several times over.  Same results within rounding (the
-     * summation order inside a window does not change; tile boundaries do
-     * not enter the arithmetic).  For tests and tuning. */
-    RIB_FLAG_BWD_WIDE = 2
+    /* Use the wide workgroups (8 waves sharing each streamed tile) whenever the
+     * window has a multiple of 512 tokens, forward and backward.  By default
+     * they are chosen only for windows of 4096 tokens or more with enough work
+     * to fill the chip several times over.  Same results within rounding (tile
+     * boundaries do not enter the arithmetic).  For tests and tuning. */
+    RIB_FLAG_WIDE = 2
 };
 
 typedef struct {

@@ -1125,7 +1125,7 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
         // tokens), which halves the staging work per wave (measured +6..10 % at N = 4096 and 9216).
         // At N = 1024 the single workgroup per CU this implies leaves the per-workgroup prologue
         // and epilogue uncovered and is slower.
-        const bool wide = (g.flags & RIB_FLAG_BWD_WIDE) != 0 || (g.N >= 4096 && g.units * (g.N / 512) >= 1024);
+        const bool wide = (g.flags & RIB_FLAG_WIDE) != 0 || (g.N >= 4096 && g.units * (g.N / 512) >= 1024);
         if (g.N % 512 == 0 && wide)
             e = launch_fast<DQK, DVK, 128, 8, XC>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
         else

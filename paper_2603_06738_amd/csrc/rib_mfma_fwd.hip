@@ -273,8 +273,13 @@ __device__ __forceinline__ void attend(const Geo &g, int hd, const TK &tok, bf16
 // so the matrix pipe and the vector ALU work on independent data all the time; the
 // staging of the next tile (global loads early, LDS writes late) rides in the gaps.
 // Scheduling fences keep the compiler from regrouping the instruction stream.
-constexpr int kFT = 128;            // keys per tile
-constexpr int kFVS = kFT + 8;       // bf16 per V^T row (272 B: conflict-free 16-byte reads)
+// The fast path runs with 4 or 8 waves per workgroup; a K/V tile holds 32 keys per wave (128 or
+// 256), so that one pass of the staging code (8 lanes per token, 4 tokens per thread) fills it.
+template <int WAVES>
+struct FastTile {
+    static constexpr int FT = 32 * WAVES;       // keys per tile
+    static constexpr int FVS = FT + 8;          // bf16 per V^T row (272 / 528 B: conflict-free 16-byte reads)
+};
 // scheduling-group masks of __builtin_amdgcn_sched_group_barrier
 #define RIB_SG_VALU 0x002
 #define RIB_SG_MFMA 0x008
@@ -320,10 +325,10 @@ struct FastConst {                  // per-thread staging constants
     int k_dst, f_dst0, f_dst1, v_dst;   // bf16 element offsets inside a stage
 };
 
-template <int DQK>
+template <int DQK, int WAVES>
 __device__ __forceinline__ FastConst<DQK> fast_const(const Geo &g, int hd)
 {
-    constexpr int KSTR = DQK + 8;
+    constexpr int KSTR = DQK + 8, kFVS = FastTile<WAVES>::FVS;
     FastConst<DQK> c;
     const int tid = threadIdx.x, grp = tid >> 3, j = tid & 7;
     const int hp = g.d >> 1, rh = g.r >> 1;             // dwords per content row / RIB row (both >= 2)
@@ -367,10 +372,10 @@ __device__ __forceinline__ void fast_load(FastRegs<DQK> &rg, const FastConst<DQK
 
 // LDS writes of token p: its pieces of the K_aug row; after the 4th token the four V^T
 // rows of this lane (4 keys per 8-byte write)
-template <int DQK>
+template <int DQK, int WAVES>
 __device__ __forceinline__ void fast_store(const FastRegs<DQK> &rg, const FastConst<DQK> &c, int p, bf16_t *Kf, bf16_t *Vf)
 {
-    constexpr int KSTR = DQK + 8;
+    constexpr int KSTR = DQK + 8, kFVS = FastTile<WAVES>::FVS;
     *(dword2 *)(Kf + c.k_dst + p * KSTR) = rg.kx[p];
     *(dword2 *)(Kf + c.f_dst0 + p * KSTR) = rg.fa[p];
     if (DQK == 64) *(dword2 *)(Kf + c.f_dst1 + p * KSTR) = rg.fb[p];
@@ -397,11 +402,12 @@ struct FastCtx {
     const char *kbase, *vbase, *fbase;
     uint32_t ftile;                 // bytes of RIB rows per tile
 };
-template <int DQK>
+template <int DQK, int WAVES>
 __device__ __forceinline__ FastCtx<DQK> fast_ctx(const Geo &g, int hd, const bf16_t *k, const bf16_t *v, const bf16_t *fk)
 {
+    constexpr int kFT = FastTile<WAVES>::FT;
     FastCtx<DQK> x;
-    x.c = fast_const<DQK>(g, hd);
+    x.c = fast_const<DQK, WAVES>(g, hd);
     x.kbase = (const char *)k;
     x.vbase = (const char *)v;
     x.fbase = (const char *)(fk + (int64_t)hd * g.N * g.r);
@@ -413,12 +419,14 @@ __device__ __forceinline__ FastCtx<DQK> fast_ctx(const Geo &g, int hd, const bf1
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #define kOnes2 __builtin_bit_cast(bf16x2, 0x3f803f80u)
 
-template <int DQK, bool ONES>
+template <int DQK, bool ONES, int WAVES>
 __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx, FastRegs<DQK> &rg, const TokMap &tok,
                                             bf16_t *Kf, bf16_t *Vf, const bf16x8 (&Q)[2][DQK / 16], f32x16 (&O)[2],
                                             float (&lsum)[2])
 {
     constexpr int KS = DQK / 16, KSTR = DQK + 8;
+    constexpr int kFT = FastTile<WAVES>::FT, kFVS = FastTile<WAVES>::FVS;
+    constexpr int NKB = kFT / 32, NSTEP = 2 * NKB;        // key blocks per tile; (key block, query block) steps
     constexpr int KSZ = kFT * KSTR, VSZ = 32 * kFVS;     // bf16 per stage
     const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
     const int ntiles = g.N / kFT;
@@ -433,7 +441,7 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
         lsum[qb] = 0.f;
     }
 #pragma unroll
-    for (int p = 0; p < 4; ++p) fast_store<DQK>(rg, c, p, Kf, Vf);
+    for (int p = 0; p < 4; ++p) fast_store<DQK, WAVES>(rg, c, p, Kf, Vf);
     {   // tile 1 goes in flight now and is written to LDS at the end of tile 0's block
         const int t1 = ntiles > 1 ? 1 : 0;
         fast_load<DQK>(rg, c, g, tok, t1 * kFT, kbase, vbase, fbase + (uint32_t)t1 * ftile);
@@ -450,7 +458,7 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
         const int nt = tile + 2 < ntiles ? tile + 2 : ntiles - 1;
         const char *fn = fbase + (uint32_t)nt * ftile;
 
-        bf16x8 Ak[4][KS], Av[4][2];
+        bf16x8 Ak[NKB][KS], Av[NKB][2];
         f32x16 S[2];
         uint4 P[2][2];          // packed bf16 probabilities: B operands of the PV MFMAs
 #pragma unroll
@@ -462,7 +470,7 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
         for (int t = 1; t < KS; ++t) S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[0][t], Q[0][t], S[0], 0, 0, 0);
 
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
+        for (int s = 0; s < NSTEP; ++s) {
             const int kb = s >> 1, qb = s & 1, cs = s & 1, ns = cs ^ 1;
             const int s1 = s + 1, kb1 = s1 >> 1, qb1 = s1 & 1;
             const int kbp = (s - 1) >> 1, qbp = (s - 1) & 1;
@@ -471,11 +479,11 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
 #pragma unroll
             for (int grp = 0; grp < 4; ++grp) {
                 if (grp < 3) {
-                    if (s < 7 && grp < 2) {
+                    if (s < NSTEP - 1 && grp < 2) {
                         S[ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[kb1][grp], Q[qb1][grp],
                                                                          grp == 0 ? zero : S[ns], 0, 0, 0);
                     }
-                    if (s < 7 && grp == 2) {
+                    if (s < NSTEP - 1 && grp == 2) {
 #pragma unroll
                         for (int t = 2; t < KS; ++t)
                             S[ns] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ak[kb1][t], Q[qb1][t], S[ns], 0, 0, 0);
@@ -503,7 +511,7 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
             }
             // group 4: second PV MFMA of the previous block + this step's share of the staging
             if (s > 0) O[qbp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[kbp][1], as_bf16x8(P[ns][1]), O[qbp], 0, 0, 0);
-            if (qb == 0 && kb + 1 < 4) {
+            if (qb == 0 && kb + 1 < NKB) {
 #pragma unroll
                 for (int t = 0; t < KS; ++t)
                     Ak[kb + 1][t] = *(const bf16x8 *)(Kc + ((kb + 1) * 32 + col) * KSTR + 16 * t + 8 * hf);
@@ -513,17 +521,17 @@ __device__ __forceinline__ void attend_fast(const Geo &g, const FastCtx<DQK> &fx
             }
         }
         // drain: PV of the last block
-        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][0], as_bf16x8(P[1][0]), O[1], 0, 0, 0);
-        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[3][1], as_bf16x8(P[1][1]), O[1], 0, 0, 0);
+        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[NKB - 1][0], as_bf16x8(P[1][0]), O[1], 0, 0, 0);
+        O[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Av[NKB - 1][1], as_bf16x8(P[1][1]), O[1], 0, 0, 0);
         // staging of the next tiles: tile+1 (requested a whole block ago) goes to LDS, then
         // tile+2 is requested into the same registers
 #pragma unroll
-        for (int p = 0; p < 4; ++p) fast_store<DQK>(rg, c, p, Kn, Vn);
+        for (int p = 0; p < 4; ++p) fast_store<DQK, WAVES>(rg, c, p, Kn, Vn);
         fast_load<DQK>(rg, c, g, tok, nt * kFT, kbase, vbase, fn);
 
         // The order the scheduler is asked to build out of the block above: every MFMA
         // followed by its share of the exp2 (transcendental) and pack (VALU) work.
-        sched_pipeline<0, 8 * (DQK / 16 + 2)>();
+        sched_pipeline<0, NSTEP * (DQK / 16 + 2)>();
         __syncthreads();
     }
 }
@@ -544,7 +552,7 @@ __device__ __forceinline__ void init_generic_tiles(const Geo &g, bf16_t *Ka, bf1
 template <int DQK, int NT, bool ONES>
 __device__ __forceinline__ void init_fast_tiles(const Geo &g, bf16_t *Kf, bf16_t *Vf)
 {
-    constexpr int KSTR = DQK + 8;
+    constexpr int KSTR = DQK + 8, kFT = FastTile<NT / 64>::FT, kFVS = FastTile<NT / 64>::FVS;
     const int pad0 = g.d + g.r;                                  // even; columns pad0..DQK-1 are zero
     for (int row = threadIdx.x; row < 2 * kFT; row += NT)
         for (int c = pad0; c < DQK; c += 2) *(uint32_t *)(Kf + row * KSTR + c) = 0u;
@@ -557,11 +565,11 @@ __device__ __forceinline__ void init_fast_tiles(const Geo &g, bf16_t *Kf, bf16_t
     }
 }
 
-template <int DQK, bool FAST>
+template <int DQK, bool FAST, int WAVES = 4>
 struct FwdSmem {
     static constexpr int KSTR = DQK + 8;
     static constexpr int GEN_K = 2 * kTK * KSTR, GEN_V = 2 * 32 * kVStr;       // bf16 elements
-    static constexpr int FAST_K = 2 * kFT * KSTR, FAST_V = 2 * 32 * kFVS;
+    static constexpr int FAST_K = 2 * FastTile<WAVES>::FT * KSTR, FAST_V = 2 * 32 * FastTile<WAVES>::FVS;
     static constexpr int TILE_ELEMS = FAST ? (FAST_K + FAST_V) : (GEN_K + GEN_V);
     static constexpr size_t TILE_BYTES = (size_t)TILE_ELEMS * sizeof(bf16_t);
 };
@@ -690,17 +698,18 @@ __global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_kernel(
 // are requested together; each wave stages its own 64 Q_aug rows), then attend_fast.
 // Rows whose softmax denominator leaves the safe range send the workgroup through the
 // max-tracking path of the general kernel.
-template <int DQK, bool ONES>
-__global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
+template <int DQK, bool ONES, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void mfma_fwd_fast_kernel(
     Geo g, int nqblk, int force_max, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
     const bf16_t *__restrict__ v, const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk,
     bf16_t *__restrict__ out, float *__restrict__ lse)
 {
-    constexpr int NT = 256, WAVES = 4;
+    constexpr int NT = WAVES * 64;
+    constexpr int kFT = FastTile<WAVES>::FT, kFVS = FastTile<WAVES>::FVS;
     constexpr int KS = DQK / 16;
     constexpr int KSTR = DQK + 8;
     using St = Stage<DQK, WAVES>;
-    using Sm = FwdSmem<DQK, true>;
+    using Sm = FwdSmem<DQK, true, WAVES>;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     bf16_t *tiles = (bf16_t *)smem;
     bf16_t *Kf = tiles, *Vf = tiles + Sm::FAST_K;
@@ -721,7 +730,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     }
     __syncthreads();
 
-    const FastCtx<DQK> fx = fast_ctx<DQK>(g, hd, k, v, fk);
+    const FastCtx<DQK> fx = fast_ctx<DQK, WAVES>(g, hd, k, v, fk);
     FastRegs<DQK> rg;
     fast_load<DQK>(rg, fx.c, g, tok, 0, fx.kbase, fx.vbase, fx.fbase);
 
@@ -767,7 +776,7 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     bool redo = force_max != 0;
     if (!redo) {
         init_fast_tiles<DQK, NT, ONES>(g, Kf, Vf);
-        attend_fast<DQK, ONES>(g, fx, rg, tok, Kf, Vf, Q, O, lsum);
+        attend_fast<DQK, ONES, WAVES>(g, fx, rg, tok, Kf, Vf, Q, O, lsum);
         bool bad = false;
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -839,34 +848,40 @@ __global__ __launch_bounds__(256, 2) void mfma_fwd_fast_kernel(
     }
 }
 
-template <int DQK, bool ONES, bool FAST>
+// WAVES = 0: the general kernel (4 waves, 64-key tiles); 4 or 8: the fast kernel.
+template <int DQK, bool ONES, int WAVES>
 hipError_t launch(const Geo &g, int force_max, const void *q, const void *k, const void *v, const void *fq,
                   const void *fk, void *out, float *lse, hipStream_t st)
 {
-    constexpr int WAVES = 4;
-    const int nqblk = (g.N + WAVES * 64 - 1) / (WAVES * 64);
+    constexpr bool FAST = WAVES != 0;
+    constexpr int NW = FAST ? WAVES : 4;
+    const int nqblk = (g.N + NW * 64 - 1) / (NW * 64);
     const int ntiles = (g.N + kTK - 1) / kTK;
-    const size_t dyn = FwdSmem<DQK, FAST>::TILE_BYTES + (FAST ? (size_t)2 * g.M : (size_t)ntiles * kTK) * sizeof(int);
+    const size_t dyn = FwdSmem<DQK, FAST, NW>::TILE_BYTES + (FAST ? (size_t)2 * g.M : (size_t)ntiles * kTK) * sizeof(int);
     if (dyn > (size_t)kMaxDynLds) return hipErrorInvalidValue;
-    auto kern = FAST ? mfma_fwd_fast_kernel<DQK, ONES> : mfma_fwd_kernel<DQK, WAVES, ONES, false>;
+    void (*kern)(Geo, int, int, const bf16_t *, const bf16_t *, const bf16_t *, const bf16_t *, const bf16_t *, bf16_t *,
+                 float *);
+    if constexpr (FAST) kern = mfma_fwd_fast_kernel<DQK, ONES, NW>;
+    else kern = mfma_fwd_kernel<DQK, 4, ONES, false>;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [kern] {
         attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
     });
     if (attr_err != hipSuccess) return attr_err;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(g.units * nqblk)), dim3(WAVES * 64), dyn, st, g, nqblk, force_max,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(g.units * nqblk)), dim3(NW * 64), dyn, st, g, nqblk, force_max,
                        (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq,
                        (const bf16_t *)fk, (bf16_t *)out, lse);
     return hipGetLastError();
 }
 
 template <int DQK, bool ONES>
-hipError_t launch_pick(const Geo &g, bool fast, int force_max, const void *q, const void *k, const void *v,
+hipError_t launch_pick(const Geo &g, int waves, int force_max, const void *q, const void *k, const void *v,
                        const void *fq, const void *fk, void *out, float *lse, hipStream_t st)
 {
-    return fast ? launch<DQK, ONES, true>(g, force_max, q, k, v, fq, fk, out, lse, st)
-                : launch<DQK, ONES, false>(g, force_max, q, k, v, fq, fk, out, lse, st);
+    if (waves == 8) return launch<DQK, ONES, 8>(g, force_max, q, k, v, fq, fk, out, lse, st);
+    if (waves == 4) return launch<DQK, ONES, 4>(g, force_max, q, k, v, fq, fk, out, lse, st);
+    return launch<DQK, ONES, 0>(g, force_max, q, k, v, fq, fk, out, lse, st);
 }
 
 }  // namespace
@@ -877,20 +892,27 @@ bool mfma_fwd_supported(const Geo &g, int dtype)
            g.N <= 9216 && (g.tstride & 1) == 0;
 }
 
-// The pipelined fast path needs whole 128-key tiles and 32-bit byte offsets built with
-// a 24-bit multiply.
-static bool fast_ok(const Geo &g)
+// The pipelined fast path needs whole tiles (128 keys with 4 waves, 256 with 8) and 32-bit byte
+// offsets built with a 24-bit multiply.  Returns the number of waves to run it with, 0 for the
+// general kernel.  Eight waves (each wave then stages half as much per key block) pay off for large
+// windows with enough workgroups to go round; at N = 1024 the one workgroup per CU they imply
+// leaves the per-workgroup prologue and epilogue uncovered.
+static int fast_waves(const Geo &g)
 {
     const int64_t tokens = (int64_t)g.B * g.H * g.W;
     const bool small_r = (g.d + g.r <= 48) ? (g.r <= 32) : true;
-    return g.r >= 4 && g.d >= 4 && g.N % kFT == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
-           tokens * g.tstride * 2 < ((int64_t)1 << 32) && small_r;
+    if (!(g.r >= 4 && g.d >= 4 && g.N % 128 == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+          tokens * g.tstride * 2 < ((int64_t)1 << 32) && small_r))
+        return 0;
+    const bool wide = (g.flags & RIB_FLAG_WIDE) != 0 || (g.N >= 4096 && g.units * (g.N / 512) >= 1024);
+    return (wide && g.N % 512 == 0) ? 8 : 4;
 }
 
 hipError_t launch_mfma_fwd(const Geo &g, int force_max, const void *q, const void *k, const void *v, const void *fq,
                            const void *fk, void *out, float *lse, hipStream_t st)
 {
-    const bool ones = g.d < 32, fast = fast_ok(g);
+    const bool ones = g.d < 32;
+    const int fast = fast_waves(g);
     if (g.d + g.r <= 48)
         return ones ? launch_pick<48, true>(g, fast, force_max, q, k, v, fq, fk, out, lse, st)
                     : launch_pick<48, false>(g, fast, force_max, q, k, v, fq, fk, out, lse, st);

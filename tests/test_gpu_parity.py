@@ -270,13 +270,14 @@ WIDE = [
 
 
 @pytest.mark.parametrize("wl", WIDE, ids=lambda w: w.name)
-def test_backward_wide_workgroups(oracle, gh, wl):
-    """The 8-wave backward kernels (default only for large windows) forced onto small problems so
-    that every variant is checked element by element; they must also agree with the 4-wave kernels
-    to within the tolerance."""
+def test_wide_workgroups(oracle, gh, wl):
+    """The 8-wave forward and backward kernels (default only for large windows) forced onto small
+    problems so that every variant is checked element by element, the forward in both softmax
+    paths."""
     x = wk.make_inputs(wl)
-    t, out, lse = _check_fwd(oracle, gh, wl, x)
-    got = gh.gpu_bwd(wl, t, out, lse, flags=rb.RIB_FLAG_BWD_WIDE)
+    _check_fwd(oracle, gh, wl, x, flags=rb.RIB_FLAG_WIDE | FORCE_MAX)
+    t, out, lse = _check_fwd(oracle, gh, wl, x, flags=rb.RIB_FLAG_WIDE)
+    got = gh.gpu_bwd(wl, t, out, lse, flags=rb.RIB_FLAG_WIDE)
     ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
     for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
         assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name

@@ -658,6 +658,15 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
     }
 }
 
+// Zero the columns of one augmented row pair that no staging code writes: [d+r, DQK) of the X row and
+// [d, DVK) of the Y row, minus the two columns that carry LSE / delta when those ride in columns.
+template <int DQK, int DVK, bool XC>
+__device__ __forceinline__ void clear_pad_columns(const Geo &g, bf16_t *xrow, bf16_t *yrow)
+{
+    for (int c = g.d + g.r; c < DQK - (XC ? 0 : 2); c += 2) *(uint32_t *)(xrow + c) = 0u;
+    for (int c = g.d; c < DVK - (XC ? 0 : 2); c += 2) *(uint32_t *)(yrow + c) = 0u;
+}
+
 // Each wave stages its own 64 stationary rows (X rows [64][XS], Y rows [64][YS], extras
 // included) into its private LDS area `W` and reads them back as MFMA B operands.
 template <int DQK, int DVK, bool QDO, bool SCALE, bool XC>
@@ -713,6 +722,9 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
         *(uint32_t *)(Xs + lane * L::XS + DQK - 2) = ex;
         *(uint32_t *)(Ys + lane * L::YS + DVK - 2) = ey;
     }
+    // the padding columns of the stationary operands must read zero: whatever a streamed tile
+    // holds in the same columns is then multiplied away
+    clear_pad_columns<DQK, DVK, XC>(g, Xs + lane * L::XS, Ys + lane * L::YS);
     __syncthreads();
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
@@ -723,51 +735,47 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
 }
 
 // ---- epilogue through LDS: the accumulator layout gives a lane 16 rows of ONE token, and
-// storing from there would touch 32 token rows per instruction.  Each wave parks its 64
-// tokens in a private LDS area -- content columns as bf16 rows of kORS elements, RIB
-// columns as fp32 rows of kFRS elements (odd dword strides: conflict-free both ways) --
-// and writes them out with 16 lanes per token.
-constexpr int kORS = 34, kFRS = 35;     // kFRS: up to 34 RIB columns (d = 30, r = 34)
-constexpr int kWaveOut = 64 * kORS * 2 + 64 * kFRS * 4;      // bytes per wave
+// storing from there would touch 32 token rows per instruction.  Each wave parks the fp32
+// accumulators of its 64 tokens in a private LDS area (rows of kARS floats: the odd stride keeps
+// the column-wise writes conflict-free) without any per-element decision, and writes them out
+// with 16 lanes per token, scaling and rounding on the way.  The area is private to the wave and
+// the LDS serves a wave's instructions in order, so no workgroup barrier is needed around it.
+constexpr int kARS = 65;
+constexpr int kWaveOut = 64 * kARS * 4;      // bytes per wave
 
-__device__ __forceinline__ void stash_aug(const f32x16 &acc, int mb, int hf, const Geo &g, float sc, float sp,
-                                          bf16_t *orow, float *frow)
+// one 32 x 32 accumulator block: this lane's token row, columns 32*mb + ...
+__device__ __forceinline__ void stash_block(const f32x16 &acc, int mb, int hf, float *arow)
 {
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) {
-        int c = 32 * mb + 8 * (i >> 2) + 4 * hf + (i & 3);
-        if (c < g.d) *(uint32_t *)(orow + c) = pack_bf16(acc[i] * sc, acc[i + 1] * sc);
-        else if (c < g.d + g.r) {
-            frow[c - g.d] = acc[i] * sp;
-            frow[c - g.d + 1] = acc[i + 1] * sp;
-        }
-    }
+    for (int i = 0; i < 16; ++i) arow[32 * mb + 8 * (i >> 2) + 4 * hf + (i & 3)] = acc[i];
 }
 
-// rows [n0, n0+64) of a grid tensor from the wave's bf16 area
-__device__ __forceinline__ void flush_rows(const bf16_t *Os, bf16_t *__restrict__ dst, const TokMap &tok, int n0, int hd,
-                                           const Geo &g)
+// columns [0, d) of rows [n0, n0+64) -> a grid tensor (bf16), times `scale`
+__device__ __forceinline__ void flush_rows(const float *As, float scale, bf16_t *__restrict__ dst, const TokMap &tok, int n0,
+                                           int hd, const Geo &g)
 {
     const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
     if (2 * j < g.d) {
 #pragma unroll
         for (int p = 0; p < 16; ++p) {
             const int row = p * 4 + sub;
-            *(uint32_t *)(dst + (int64_t)tok[n0 + row] * g.C + hd * g.d + 2 * j) = *(const uint32_t *)(Os + row * kORS + 2 * j);
+            const float a = As[row * kARS + 2 * j] * scale, b = As[row * kARS + 2 * j + 1] * scale;
+            *(uint32_t *)(dst + (int64_t)tok[n0 + row] * g.C + hd * g.d + 2 * j) = pack_bf16(a, b);
         }
     }
 }
 
-// rows [n0, n0+64) of this unit's RIB partial (contiguous in memory) from the wave's fp32 area
-__device__ __forceinline__ void flush_partial(const float *Fs, float *__restrict__ part, int r)
+// columns [d, d+r) of rows [n0, n0+64) -> this unit's RIB partial (contiguous in memory), times `scale`
+__device__ __forceinline__ void flush_partial(const float *As, float scale, float *__restrict__ part, const Geo &g)
 {
-    const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
+    const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15, r = g.r;
+    const float *Fs = As + g.d;
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
         const int row = p * 4 + sub;
-        if (j < r) part[row * r + j] = Fs[row * kFRS + j];
-        if (16 + j < r) part[row * r + 16 + j] = Fs[row * kFRS + 16 + j];
-        if (32 + j < r) part[row * r + 32 + j] = Fs[row * kFRS + 32 + j];
+        if (j < r) part[row * r + j] = Fs[row * kARS + j] * scale;
+        if (16 + j < r) part[row * r + 16 + j] = Fs[row * kARS + 16 + j] * scale;
+        if (32 + j < r) part[row * r + 32 + j] = Fs[row * kARS + 32 + j] * scale;
     }
 }
 
@@ -782,11 +790,16 @@ struct FSmem {
     static constexpr size_t BYTES = (size_t)ELEMS16 * sizeof(bf16_t);
 };
 
-template <int NT>
-__device__ __forceinline__ void zero_lds(bf16_t *base, int elems16)
+// padding columns of the row images of both stages (see clear_pad_columns)
+template <int DQK, int DVK, int T, int NT, bool XC>
+__device__ __forceinline__ void clear_stage_pads(const Geo &g, bf16_t *stage0, bf16_t *stage1)
 {
-    const uint4 z = {0u, 0u, 0u, 0u};
-    for (int e = threadIdx.x; e < elems16 / 8; e += NT) ((uint4 *)base)[e] = z;
+    using L = LayT<DQK, DVK, T>;
+    for (int e = threadIdx.x; e < 2 * T; e += NT) {
+        bf16_t *st = e < T ? stage0 : stage1;
+        const int row = e < T ? e : e - T;
+        clear_pad_columns<DQK, DVK, XC>(g, st + L::XR + row * L::XS, st + L::YR + row * L::YS);
+    }
 }
 
 __device__ __forceinline__ void block_coords(const Geo &g, int nblk, int64_t &u, int &blk, int &w, int &hd)
@@ -820,7 +833,6 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
     const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
 
     const TokMap tok = fill_tok_map<kNT>(g, w, (int *)(smem + Sm::ELEMS16));
-    zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
 
     const FConst<DQK, DVK, T> c = fconst<DQK, DVK, T>(g, hd, threadIdx.x);
@@ -833,10 +845,11 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
     stationary_rows<DQK, DVK, true, true, XC>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
                                     smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb);
-    // No second clearing: from here on the padding columns of a streamed tile may hold stale
-    // (finite) rows of this workgroup; they only ever multiply the zero padding of the
-    // stationary operands, and stale transposed rows only feed accumulator rows that are
-    // never stored.
+    // LDS is not cleared wholesale.  The padding columns of the streamed row images only ever
+    // multiply the zero padding of the stationary operands, but they must be finite for that:
+    // they are zeroed once here, in both stages (nothing writes them afterwards).  Unwritten rows
+    // of the transposed images only feed accumulator rows that are never stored.
+    clear_stage_pads<DQK, DVK, T, kNT, XC>(g, stage0, stage1);
     fstore<DQK, DVK, T, false, false, false, XC>(rg, c, stage0, 1.f, 1.f);
     fload<DQK, DVK, T, false>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, kb, vb, fkb, lse, delta);
     __syncthreads();
@@ -903,17 +916,14 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
     }
 
     // (the loop's last barrier has passed: the tiles are free)
-    bf16_t *Os = (bf16_t *)((char *)smem + wave * kWaveOut);
-    float *Fs = (float *)(Os + 64 * kORS);
+    float *As = (float *)((char *)smem + wave * kWaveOut);
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-            stash_aug(acc[qb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain,
-                      Os + (qb * 32 + col) * kORS, Fs + (qb * 32 + col) * kFRS);
-    __syncthreads();
-    flush_rows(Os, dq, tok, q0, hd, g);
-    flush_partial(Fs, dfq_part + (u * g.N + q0) * g.r, g.r);
+        for (int mb = 0; mb < 2; ++mb) stash_block(acc[qb][mb], mb, hf, As + (qb * 32 + col) * kARS);
+    __builtin_amdgcn_wave_barrier();
+    flush_rows(As, g.scale_c * kTruncGain, dq, tok, q0, hd, g);
+    flush_partial(As, g.scale_p * kTruncGain, dfq_part + (u * g.N + q0) * g.r, g);
 }
 
 // dK, dV (+ dF_k partial), fast path.
@@ -938,7 +948,6 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
     const float sc2 = g.scale_c * kLog2e, sp2 = g.scale_p * kLog2e;
 
     const TokMap tok = fill_tok_map<kNT>(g, w, (int *)(smem + Sm::ELEMS16));
-    zero_lds<kNT>(smem, Sm::ELEMS16);
     __syncthreads();
 
     const FConst<DQK, DVK, T> c = fconst<DQK, DVK, T>(g, hd, threadIdx.x);
@@ -951,6 +960,7 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
     bf16x8 Kb[2][L::KS], Vb[2][L::VS];
     stationary_rows<DQK, DVK, false, true, XC>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, sc2, sp2,
                                      smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
+    clear_stage_pads<DQK, DVK, T, kNT, XC>(g, stage0, stage1);
     fstore<DQK, DVK, T, true, true, false, XC>(rg, c, stage0, sc2, sp2);
     fload<DQK, DVK, T, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
     __syncthreads();
@@ -1044,36 +1054,26 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
         __syncthreads();
     }
 
-    bf16_t *Os = (bf16_t *)((char *)smem + wave * kWaveOut);
-    float *Fs = (float *)(Os + 64 * kORS);
+    float *As = (float *)((char *)smem + wave * kWaveOut);
     // dK and the dF_k partial first, then dV through the same area
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-            stash_aug(accK[kb][mb], mb, hf, g, g.scale_c * kTruncGain, g.scale_p * kTruncGain,
-                      Os + (kb * 32 + col) * kORS, Fs + (kb * 32 + col) * kFRS);
-    __syncthreads();
-    flush_rows(Os, dk, tok, k0, hd, g);
-    flush_partial(Fs, dfk_part + (u * g.N + k0) * g.r, g.r);
-    __syncthreads();
+        for (int mb = 0; mb < 2; ++mb) stash_block(accK[kb][mb], mb, hf, As + (kb * 32 + col) * kARS);
+    __builtin_amdgcn_wave_barrier();
+    flush_rows(As, g.scale_c * kTruncGain, dk, tok, k0, hd, g);
+    flush_partial(As, g.scale_p * kTruncGain, dfk_part + (u * g.N + k0) * g.r, g);
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-            int cc = 8 * (i >> 2) + 4 * hf + (i & 3);
-            *(uint32_t *)(Os + (kb * 32 + col) * kORS + cc) =
-                pack_bf16(accV[kb][i] * kTruncGain, accV[kb][i + 1] * kTruncGain);
-        }
-    }
-    __syncthreads();
-    flush_rows(Os, dv, tok, k0, hd, g);
+    for (int kb = 0; kb < 2; ++kb) stash_block(accV[kb], 0, hf, As + (kb * 32 + col) * kARS);
+    __builtin_amdgcn_wave_barrier();
+    flush_rows(As, kTruncGain, dv, tok, k0, hd, g);
 }
 
 static bool bwd_fast_ok(const Geo &g)
 {
     const int64_t tokens = (int64_t)g.B * g.H * g.W;
-    return g.r > 0 && g.r < kFRS && g.N % 256 == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
+    return g.r > 0 && g.r <= 34 && g.N % 256 == 0 && tokens < (1 << 24) && g.tstride * 2 < (1 << 24) &&
            tokens * g.tstride * 2 < ((int64_t)1 << 32);
 }
 

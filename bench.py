@@ -296,6 +296,14 @@ def main():
             del r2
             torch.cuda.empty_cache()
         res["schedule"] = sched
+        # one SST+ block = its six attention layers (windows 16, 32, 48, 32, 48, 96; ranks 18, 18, 18, 34, 34, 34)
+        stack = ["sst-m16-r18", "sst-m32-r18", "sst-m48-r18", "sst-m32-r34", "sst-m48-r34", "sst-m96-r34"]
+        f_ms = sum(sched[n]["fwd_ms"] for n in stack)
+        b_ms = sum(sched[n]["bwd_ms"] for n in stack)
+        flop = sum(wk.SCHEDULE[n].fwd_flop + wk.SCHEDULE[n].bwd_flop for n in stack)
+        res["sst_plus_block"] = {"layers": stack, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
+                                 "tflops": round(flop / ((f_ms + b_ms) * 1e-3) / 1e12, 1),
+                                 "tokens_per_s": round(wk.SCHEDULE[stack[0]].tokens / ((f_ms + b_ms) * 1e-3), 1)}
         res["generator"] = time_generator(rb, torch)
         res["gated_c5"] = time_gated(rb, torch, wk.WORKLOADS["c5"])
 

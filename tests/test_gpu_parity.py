@@ -201,8 +201,9 @@ GATED = [
 ]
 
 
+@pytest.mark.parametrize("flags", [0, rb.RIB_FLAG_WIDE], ids=["default", "wide"])
 @pytest.mark.parametrize("wl", GATED, ids=lambda w: w.name)
-def test_gated_forward_and_backward(oracle, gh, wl):
+def test_gated_forward_and_backward(oracle, gh, wl, flags):
     """CLA gate (Eq. 9) fused into the epilogue, and the gated backward (dO = dO' * G and
     dG = dO' * O formed in the delta pass).  Bounds: the north-star tolerance for every tensor;
     for dG the forward's error in O is multiplied by dO', hence tol * max(1, max|dO'|)."""
@@ -214,7 +215,7 @@ def test_gated_forward_and_backward(oracle, gh, wl):
     ref = oracle.gated_bwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], gate, x["d_out"])
     t = gh.device_inputs(wl, x)
     tg = rb.to_device(gate, wl.dtype, gh.DEV)
-    p = rb.params_of(wl)
+    p = rb.params_of(wl, flags=flags)
     td = gh.tdtype(wl)
     grid = (wl.B, wl.H, wl.W, wl.C)
     nan = float("nan")

@@ -84,7 +84,10 @@ enum {
      * they are chosen only for windows of 4096 tokens or more with enough work
      * to fill the chip several times over.  Same results within rounding (tile
      * boundaries do not enter the arithmetic).  For tests and tuning. */
-    RIB_FLAG_WIDE = 2
+    RIB_FLAG_WIDE = 2,
+    /* Run on the vector-ALU kernels even where a matrix-core kernel serves the
+     * problem.  Same results within rounding; for tests and comparisons. */
+    RIB_FLAG_VECTOR_ONLY = 4
 };
 
 typedef struct {
@@ -100,7 +103,8 @@ typedef struct {
 } rib_params;
 
 /* Built for: 1 <= d <= 64, 0 <= r <= 64, any window side M with M*M <= 65536.
- * bf16 problems with d <= 32 and d + r <= 64 run on the matrix-core kernels;
+ * Problems with d <= 32 and d + r <= 64 run on the matrix-core kernels (bf16
+ * storage: bf16 MFMA with fp32 accumulation; fp32 storage: fp32 MFMA);
  * everything else runs on a slower fp32 vector-ALU kernel with the same results. */
 
 /* Forward:  out[B][H][W][C]  (dtype of q),  lse[B*nW][heads][N] fp32 or NULL.

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(_HERE, "librib_attn.so")
 RIB_F32, RIB_BF16 = 0, 1
 RIB_FLAG_FORCE_ROW_MAX = 1
 RIB_FLAG_WIDE = 2
+RIB_FLAG_VECTOR_ONLY = 4
 
 RIB_OK = 0
 STATUS_NAMES = {0: "RIB_OK", 1: "RIB_ERR_NULL", 2: "RIB_ERR_SHAPE", 3: "RIB_ERR_DTYPE",

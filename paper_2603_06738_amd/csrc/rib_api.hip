@@ -70,6 +70,7 @@ const char *rib_window_attn_kernel_name(const rib_params *p, int backward)
     if (make_geo(p, &g) != RIB_OK) return nullptr;
     if (!backward && mfma_fwd_supported(g, p->dtype)) return "mfma-bf16";
     if (backward && mfma_bwd_supported(g, p->dtype)) return "mfma-bf16";
+    if (mfma_f32_supported(g, p->dtype)) return "mfma-f32";
     return "valu-f32";
 }
 
@@ -85,6 +86,8 @@ rib_status rib_window_attn_fwd(const rib_params *p, const void *q, const void *k
     if (mfma_fwd_supported(g, p->dtype))
         e = launch_mfma_fwd(g, (p->flags & RIB_FLAG_FORCE_ROW_MAX) != 0, q, k, v, f_q, f_k, out, lse,
                             (hipStream_t)stream);
+    else if (mfma_f32_supported(g, p->dtype))
+        e = launch_mfma_f32_fwd(g, q, k, v, f_q, f_k, out, lse, (hipStream_t)stream);
     else
         e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out, lse, (hipStream_t)stream);
     return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
@@ -105,6 +108,8 @@ rib_status rib_window_attn_gated_fwd(const rib_params *p, const void *q, const v
     if (mfma_fwd_supported(g, p->dtype))
         e = launch_mfma_fwd(g, (p->flags & RIB_FLAG_FORCE_ROW_MAX) != 0, q, k, v, f_q, f_k, out_gated, lse,
                             (hipStream_t)stream);
+    else if (mfma_f32_supported(g, p->dtype))
+        e = launch_mfma_f32_fwd(g, q, k, v, f_q, f_k, out_gated, lse, (hipStream_t)stream);
     else
         e = launch_valu_fwd(g, p->dtype, q, k, v, f_q, f_k, out_gated, lse, (hipStream_t)stream);
     return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
@@ -138,6 +143,9 @@ rib_status rib_window_attn_gated_bwd(const rib_params *p, const void *q, const v
     if (mfma_bwd_supported(g, p->dtype))
         e = launch_mfma_bwd(g, q, k, v, f_q, f_k, out_raw, d_out_gated, lse, dq, dk, dv, df_q, df_k, workspace,
                             (hipStream_t)stream, d_out, dgate);
+    else if (mfma_f32_supported(g, p->dtype))
+        e = launch_mfma_f32_bwd(g, q, k, v, f_q, f_k, out_raw, d_out_gated, lse, dq, dk, dv, df_q, df_k, workspace,
+                                (hipStream_t)stream, d_out, dgate);
     else
         e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out_raw, d_out_gated, lse, dq, dk, dv, df_q, df_k, workspace,
                             (hipStream_t)stream, d_out, dgate);
@@ -167,6 +175,9 @@ rib_status rib_window_attn_bwd(const rib_params *p, const void *q, const void *k
     if (mfma_bwd_supported(g, p->dtype))
         e = launch_mfma_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
                             (hipStream_t)stream);
+    else if (mfma_f32_supported(g, p->dtype))
+        e = launch_mfma_f32_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
+                                (hipStream_t)stream);
     else
         e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
                             (hipStream_t)stream);

@@ -172,6 +172,14 @@ hipError_t launch_mfma_bwd(const Geo &g, const void *q, const void *k, const voi
                            const void *fk, const void *out, const void *dout, const float *lse, void *dq,
                            void *dk, void *dv, float *dfq, float *dfk, void *ws, hipStream_t st,
                            void *gated_dout = nullptr, void *dgate = nullptr);
+// Matrix-core kernels for fp32 storage (fp32 MFMA, fp32 throughout), forward and backward.
+bool mfma_f32_supported(const Geo &g, int dtype);
+hipError_t launch_mfma_f32_fwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq,
+                               const void *fk, void *out, float *lse, hipStream_t st);
+hipError_t launch_mfma_f32_bwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq,
+                               const void *fk, const void *out, const void *dout, const float *lse, void *dq, void *dk,
+                               void *dv, float *dfq, float *dfk, void *ws, hipStream_t st, void *gated_dout = nullptr,
+                               void *dgate = nullptr);
 // With g.gate set, `dout` is the gradient of the GATED output: the launchers above first run
 // launch_delta_gated (delta, dO into gated_dout, dgate) and feed gated_dout to the main kernels.
 

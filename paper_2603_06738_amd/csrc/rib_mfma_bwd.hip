@@ -1177,7 +1177,7 @@ static bool columns_are_free(const Geo &g)
 
 bool mfma_bwd_supported(const Geo &g, int dtype)
 {
-    if (!(dtype == RIB_BF16 && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 && g.N >= 64 && g.N <= 9216 &&
+    if (!(dtype == RIB_BF16 && !(g.flags & RIB_FLAG_VECTOR_ONLY) && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 && g.N >= 64 && g.N <= 9216 &&
           (g.tstride & 1) == 0))
         return false;
     return bwd_fast_ok(g) ? g.d + g.r <= 64 : g.d + g.r + 2 <= 64;

@@ -888,8 +888,8 @@ hipError_t launch_pick(const Geo &g, int waves, int force_max, const void *q, co
 
 bool mfma_fwd_supported(const Geo &g, int dtype)
 {
-    return dtype == RIB_BF16 && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 && g.d + g.r <= 64 && g.N >= 64 &&
-           g.N <= 9216 && (g.tstride & 1) == 0;
+    return dtype == RIB_BF16 && !(g.flags & RIB_FLAG_VECTOR_ONLY) && g.d <= 32 && (g.d & 1) == 0 && (g.r & 1) == 0 &&
+           g.d + g.r <= 64 && g.N >= 64 && g.N <= 9216 && (g.tstride & 1) == 0;
 }
 
 // The pipelined fast path needs whole tiles (128 keys with 4 waves, 256 with 8) and 32-bit byte

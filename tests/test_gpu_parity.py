@@ -311,3 +311,91 @@ def test_corner_shapes(oracle, gh, wl):
     names = ("dQ", "dK", "dV", "dF_q", "dF_k") if wl.r > 0 else ("dQ", "dK", "dV")
     for name, a, b in zip(names, got, ref):
         assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name
+
+
+# --- fp32 storage on the matrix cores, and the flag that keeps any problem on the vector ALU ---
+
+VECTOR_ONLY = rb.RIB_FLAG_VECTOR_ONLY
+
+
+def test_kernel_families_by_dtype_and_flag():
+    """Which kernel family serves what: bf16 and fp32 problems with d <= 32, d + r <= 64 on their
+    matrix-core kernels, everything under RIB_FLAG_VECTOR_ONLY (and shapes outside those ranges)
+    on the vector ALU."""
+    for dt, fam in (("bf16", "mfma-bf16"), ("f32", "mfma-f32")):
+        wl = wk.custom("fam", dt, 1, 16, 16, 2, 30, 16, 16, 0, 1)
+        for back in (False, True):
+            assert rb.kernel_name(rb.params_of(wl), back) == fam
+            assert rb.kernel_name(rb.params_of(wl, flags=VECTOR_ONLY), back) == "valu-f32"
+        wide = wk.custom("fam-d64", dt, 1, 8, 8, 1, 64, 64, 8, 0, 1)
+        assert rb.kernel_name(rb.params_of(wide)) == "valu-f32"
+    tiny = wk.custom("fam-m5", "f32", 1, 5, 5, 1, 30, 16, 5, 0, 1)     # 25 tokens: below one 32-token block
+    assert rb.kernel_name(rb.params_of(tiny)) == "valu-f32"
+
+
+@pytest.mark.parametrize("wl", [w for w in SMALL if w.N >= 32 and w.d <= 32 and w.d + w.r <= 64],
+                         ids=lambda w: w.name)
+def test_vector_alu_kernels_where_the_matrix_cores_would_serve(oracle, gh, wl):
+    """The vector-ALU kernels on the shapes they no longer get by default: forward and backward."""
+    x = wk.make_inputs(wl, with_dout=True)
+    t, out, lse = _check_fwd(oracle, gh, wl, x, flags=VECTOR_ONLY)
+    got = gh.gpu_bwd(wl, t, out, lse, flags=VECTOR_ONLY)
+    ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+        assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name
+
+
+F32_MATRIX = [
+    # (B, H, W, heads, d, r, M, s): ragged tails in the stationary block (N % 128), the streamed tile (N % 64)
+    # and the 32-token block (N % 32); every padded width 16 / 32 / 48 / 64; d + r at both ends of a width
+    wk.custom("f32-m6", "f32", 2, 12, 6, 2, 8, 4, 6, 1, 401, backward=True),              # N = 36, width 16
+    wk.custom("f32-m7", "f32", 1, 7, 14, 3, 5, 11, 7, 3, 402, backward=True),             # N = 49, odd d and r, width 16
+    wk.custom("f32-m10", "f32", 1, 10, 20, 2, 17, 1, 10, 9, 403, backward=True),          # N = 100, width 32
+    wk.custom("f32-m13", "f32", 1, 13, 13, 2, 31, 33, 13, 6, 404, backward=True),         # N = 169, d + r = 64
+    wk.custom("f32-m20", "f32", 1, 20, 40, 2, 32, 0, 20, 10, 405, backward=True),         # N = 400, r = 0, d = 32
+    wk.custom("f32-m24", "f32", 1, 24, 24, 2, 30, 19, 24, 23, 406, backward=True),        # N = 576, d + r = 49 -> width 64
+    wk.custom("f32-m32", "f32", 1, 32, 64, 3, 30, 16, 32, 16, 407, backward=True),        # config 3 / 5 head, fp32
+    wk.custom("f32-m48", "f32", 1, 48, 48, 2, 30, 34, 48, 24, 408, backward=True,
+              scale_c=1 / math.sqrt(30), scale_p=1 / math.sqrt(34)),                      # N = 2304, paper's scales
+]
+
+
+@pytest.mark.parametrize("wl", F32_MATRIX, ids=lambda w: w.name)
+def test_f32_matrix_core_kernels(oracle, gh, wl):
+    """fp32 problems on the fp32 MFMA kernels: forward (O, LSE) and backward, every element, 1e-4."""
+    assert rb.kernel_name(rb.params_of(wl)) == "mfma-f32" and rb.kernel_name(rb.params_of(wl), True) == "mfma-f32"
+    x = wk.make_inputs(wl)
+    t, out, lse = _check_fwd(oracle, gh, wl, x)
+    got = gh.gpu_bwd(wl, t, out, lse)
+    ref = oracle.bwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    names = ("dQ", "dK", "dV", "dF_q", "dF_k") if wl.r > 0 else ("dQ", "dK", "dV")
+    for name, a, b in zip(names, got, ref):
+        assert gh.max_abs(gh.host(a), b) <= gh.TOL[wl.dtype], name
+
+
+def test_f32_training_shape_sampled_units(oracle, gh):
+    """Config 5's shape in fp32 storage (the paper trains in fp32), full size: forward on sampled
+    units, backward on every element (the RIB gradients sum 144 windows), and a rerun of the
+    backward must reproduce the first run bit for bit (fixed summation order)."""
+    from dataclasses import replace
+    wl = replace(wk.WORKLOADS["c5"], name="c5-f32", dtype="f32")
+    x = wk.make_inputs(wl)
+    g = geometry(oracle, wl)
+    rng = np.random.default_rng(wl.seed)
+    units = sorted({0, wl.n_units - 1, *rng.choice(wl.n_units, 3, replace=False).tolist()})
+    O_ref, lse_ref = oracle.fwd_units(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], units)
+    t = gh.device_inputs(wl, x)
+    out, lse = gh.gpu_fwd(wl, t)
+    out_h, lse_h = gh.host(out), gh.host(lse)
+    for a, u in enumerate(units):
+        assert gh.max_abs(gh.gather_unit(oracle, g, out_h, u), O_ref[a]) <= 1e-4, u
+        assert gh.max_abs(lse_h[u // wl.heads, u % wl.heads], lse_ref[a]) <= 1e-4, u
+    got = gh.gpu_bwd(wl, t, out, lse)
+    again = gh.gpu_bwd(wl, t, out, lse)
+    for a, b in zip(got, again):
+        assert bool((a == b).all())
+    ref = oracle.bwd(g, x["q"], x["k"], x["v"], x["f_q"], x["f_k"], x["d_out"])
+    for name, a, b in zip(("dQ", "dK", "dV", "dF_q", "dF_k"), got, ref):
+        err = gh.max_abs(gh.host(a), b)
+        print(f"c5-f32 {name}: max abs err {err:.3e} (largest reference magnitude {np.abs(b).max():.3g})", flush=True)
+        assert err <= 1e-4, name

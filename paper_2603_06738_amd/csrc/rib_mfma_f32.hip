@@ -39,23 +39,32 @@ __device__ __forceinline__ f32x16 mfma(float a, float b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
+// Eight A operands read ahead of the MFMA sequence that consumes them.
+struct Pre {
+    float v[8];
+};
+
 // acc += sum over i < CNT of A_i * B_i, where a_at(i) reads lane-wise A operands from LDS and
-// b_at(i) names a register.  The A operands are read eight MFMAs ahead into a second register
-// set; the scheduling barriers keep the compiler from hoisting every read of a 100-MFMA block
-// to its top (which costs more registers than there are).
-template <int CNT, class AF, class BF>
-__device__ __forceinline__ void mfma_seq(f32x16 &acc, AF a_at, BF b_at)
+// b_at(i) names a register.  `pre` holds A_0..A_7 on entry; the operands of each further group of
+// eight are read while the group before runs, and during the last group load_next(pre) reads the
+// first eight operands of whatever sequence follows, so that a wave's matrix pipe never waits for
+// LDS between sequences.  The scheduling barriers keep the compiler from hoisting every read of a
+// 100-MFMA block to its top (which costs more registers than there are).
+template <int CNT, class AF, class BF, class NF>
+__device__ __forceinline__ void mfma_seq(f32x16 &acc, Pre &pre, AF a_at, BF b_at, NF load_next)
 {
     constexpr int GS = 8, NG = CNT / GS;
     static_assert(CNT % GS == 0, "whole groups");
     float buf[2][GS];
 #pragma unroll
-    for (int i = 0; i < GS; ++i) buf[0][i] = a_at(i);
+    for (int i = 0; i < GS; ++i) buf[0][i] = pre.v[i];
 #pragma unroll
     for (int gi = 0; gi < NG; ++gi) {
         if (gi + 1 < NG) {
 #pragma unroll
             for (int i = 0; i < GS; ++i) buf[(gi + 1) & 1][i] = a_at((gi + 1) * GS + i);
+        } else {
+            load_next(pre);
         }
 #pragma unroll
         for (int i = 0; i < GS; ++i) acc = mfma(buf[gi & 1][i], b_at(gi * GS + i), acc);
@@ -77,40 +86,40 @@ __device__ __forceinline__ float aug_elem(const Geo &g, int hd, int n, int tk, c
 
 // Registers that hold one streamed tile on its way from global memory to LDS.  Lane mapping of
 // the grid tensors: lane (jj = tid / 32, c = tid % 32) fetches channel c of tokens jj, jj + 8, ...
-// (whole token rows per wave pass, one predicate per lane); the RIB features of the tile's
-// tokens are one contiguous run of 64 r floats, fetched linearly.
+// (whole token rows per wave pass); the RIB features of the tile's tokens are one contiguous
+// run of 64 r floats, fetched linearly.
 template <int DA>
 struct TileRegs {
     static constexpr int FP = DA / 4;       // passes over the RIB run: 64 * r <= 64 * DA values, 256 per pass
     float xc[8], y[8], xf[FP], e0;
 };
 
-// Request tile j0: content channels of x (token stride xstride), RIB features f and the value-side
-// tensor y (stride ystride); for the key-side kernel also the tokens' LSE (times log2 e) and delta.
+// The image a window lies in: base pointers of its tokens and the first token's index, so that
+// offsets inside the image fit 32 bits (checked on the host).
+struct ImgBase {
+    const char *x, *y;      // streamed grid tensors, at the image's first token
+    int tok0;               // b * H * W
+};
+
+// Request tile j0: content channels of x (token stride xs4 bytes), RIB features f and the value-side
+// tensor y (stride ys4 bytes); for the key-side kernel also the tokens' LSE (times log2 e) and delta.
+// Lanes beyond d and tokens beyond N fetch a clamped address (no divergent branches around the
+// loads); tile_commit writes zeros for them.
 template <int DA, bool EXTRA>
 __device__ __forceinline__ void tile_request(TileRegs<DA> &rg, const Geo &g, int hd, int64_t u, int j0, const TokMap &tok,
-                                             const float *__restrict__ x, int64_t xstride, const float *__restrict__ f,
-                                             const float *__restrict__ y, int64_t ystride,
+                                             const ImgBase &ib, uint32_t xs4, uint32_t ys4, const float *__restrict__ f,
                                              const float *__restrict__ lse, const float *__restrict__ delta)
 {
     const int tid = threadIdx.x, jj = tid >> 5, c = tid & 31;
     const int valid = g.N - j0 < kTS ? g.N - j0 : kTS;
+    const uint32_t ch4 = (uint32_t)(hd * g.d + (c < g.d ? c : g.d - 1)) * 4u;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-        rg.xc[p] = 0.f;
-        rg.y[p] = 0.f;
-    }
-    if (c < g.d) {
-        const float *xb = x + hd * g.d + c, *yb = y + hd * g.d + c;
-#pragma unroll
-        for (int p = 0; p < 8; ++p) {
-            const int n = jj + 8 * p;
-            if (n < valid) {
-                const int64_t tk = tok[j0 + n];
-                rg.xc[p] = xb[tk * xstride];
-                rg.y[p] = yb[tk * ystride];
-            }
-        }
+        int n = jj + 8 * p;
+        n = n < valid ? n : valid - 1;
+        const uint32_t t = (uint32_t)(tok[j0 + n] - ib.tok0);
+        rg.xc[p] = *(const float *)(ib.x + (t * xs4 + ch4));
+        rg.y[p] = *(const float *)(ib.y + (t * ys4 + ch4));
     }
     const int cnt = valid * g.r;
     const float *fb = f + ((int64_t)hd * g.N + j0) * g.r;
@@ -127,17 +136,20 @@ __device__ __forceinline__ void tile_request(TileRegs<DA> &rg, const Geo &g, int
     }
 }
 
-// Write the requested tile to LDS, content channels scaled by sc and RIB features by sp.
-// inv_r = ceil(2^32 / r) turns the position in the RIB run into (token, feature).
-template <int DA, bool EXTRA>
-__device__ __forceinline__ void tile_commit(const TileRegs<DA> &rg, const Geo &g, uint32_t inv_r, float sc, float sp,
+// Write the requested tile (it started at token j0) to LDS, content channels scaled by sc and RIB
+// features by sp.  inv_r = ceil(2^32 / r) turns the position in the RIB run into (token, feature).
+template <int DA, int XS, bool EXTRA>
+__device__ __forceinline__ void tile_commit(const TileRegs<DA> &rg, const Geo &g, int j0, uint32_t inv_r, float sc, float sp,
                                             float *Xs, float *Ys, float *Es)
 {
     const int tid = threadIdx.x, jj = tid >> 5, c = tid & 31;
+    const int valid = g.N - j0 < kTS ? g.N - j0 : kTS;
+    const bool cv = c < g.d;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
-        if (c < g.d) Xs[(jj + 8 * p) * kXS + c] = rg.xc[p] * sc;
-        Ys[(jj + 8 * p) * kYS + c] = rg.y[p];
+        const bool ok = cv && jj + 8 * p < valid;
+        if (cv) Xs[(jj + 8 * p) * XS + c] = ok ? rg.xc[p] * sc : 0.f;
+        Ys[(jj + 8 * p) * kYS + c] = ok ? rg.y[p] : 0.f;
     }
     const int cnt = kTS * g.r;
 #pragma unroll
@@ -145,7 +157,7 @@ __device__ __forceinline__ void tile_commit(const TileRegs<DA> &rg, const Geo &g
         const int idx = p * kNT + tid;
         if (idx < cnt) {
             const int tkn = g.r == 1 ? idx : (int)__umulhi((uint32_t)idx, inv_r);     // 2^32 / 1 does not fit
-            Xs[tkn * kXS + g.d + (idx - tkn * g.r)] = rg.xf[p] * sp;
+            Xs[tkn * XS + g.d + (idx - tkn * g.r)] = rg.xf[p] * sp;
         }
     }
     if (EXTRA && tid < 128) Es[tid] = rg.e0;       // [0, 64) LSE * log2 e, [64, 128) delta
@@ -161,27 +173,33 @@ __device__ __forceinline__ void unit_of_block(int nblk, int64_t &u, int &blk)
     blk = logical - (int)(u * nblk);
 }
 
+// Two stages of the streamed tile: while the waves work on one, the next is written to the other,
+// one workgroup barrier per tile.  XS = row stride of the augmented tile (odd).
+template <int XS>
 struct Smem {
-    float X[kTS * kXS];
-    float Y[kTS * kYS];
-    float E[128];
+    float X[2][kTS * XS];
+    float Y[2][kTS * kYS];
+    float E[2][128];
     __attribute__((aligned(16))) int tokl[512];
 };
 
-__device__ __forceinline__ void zero_x_tile(float *Xs)
+// The staging code never writes columns d + r and up of the augmented tiles: they must read as zero.
+template <int XS>
+__device__ __forceinline__ void zero_x_tiles(float *Xs)
 {
-    for (int e = threadIdx.x; e < kTS * kXS; e += kNT) Xs[e] = 0.f;
+    for (int e = threadIdx.x; e < 2 * kTS * XS; e += kNT) Xs[e] = 0.f;
 }
 
 // Forward: Q_aug rows stationary (pre-multiplied by the scales and log2 e), K_aug / V streamed;
-// online softmax with the running row max per lane.
+// online softmax with the running row max per lane.  Three workgroups per CU.
 template <int DA>
-__global__ __launch_bounds__(kNT, 2) void mfma_f32_fwd_kernel(Geo g, int nblk, uint32_t inv_r, const float *__restrict__ q,
+__global__ __launch_bounds__(kNT, 3) void mfma_f32_fwd_kernel(Geo g, int nblk, uint32_t inv_r, const float *__restrict__ q,
                                                                const float *__restrict__ k, const float *__restrict__ v,
                                                                const float *__restrict__ fq, const float *__restrict__ fk,
                                                                float *__restrict__ out, float *__restrict__ lse)
 {
-    __shared__ Smem sm;
+    constexpr int XS = DA + 1;
+    __shared__ Smem<XS> sm;
     int64_t u;
     int blk;
     unit_of_block(nblk, u, blk);
@@ -189,8 +207,15 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_fwd_kernel(Geo g, int nblk, u
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
 
     const TokMap tok = fill_tok_map<kNT>(g, w, sm.tokl);
-    zero_x_tile(sm.X);      // columns d + r .. DA - 1 are never written and must read as zero
+    zero_x_tiles<XS>(sm.X[0]);
     __syncthreads();
+
+    const int nt = (g.N + kTS - 1) / kTS;
+    const int tok0 = (w / (g.nwx * g.nwy)) * g.H * g.W;
+    const uint32_t ts4 = (uint32_t)g.tstride * 4u;
+    const ImgBase ib = {(const char *)(k + (int64_t)tok0 * g.tstride), (const char *)(v + (int64_t)tok0 * g.tstride), tok0};
+    TileRegs<DA> rg;
+    tile_request<DA, false>(rg, g, hd, u, 0, tok, ib, ts4, ts4, fk, nullptr, nullptr);
 
     const int qi = blk * kRowsWg + wave * 32 + col;
     const bool live = qi < g.N;
@@ -201,28 +226,34 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_fwd_kernel(Geo g, int nblk, u
     for (int t = 0; t < DA / 2; ++t)
         Qr[t] = aug_elem(g, hd, qc, tq, q, g.tstride, fq, g.scale_c * kLog2e, g.scale_p * kLog2e, 2 * t + hf);
 
-    TileRegs<DA> rg;
-    tile_request<DA, false>(rg, g, hd, u, 0, tok, k, g.tstride, fk, v, g.tstride, nullptr, nullptr);
+    tile_commit<DA, XS, false>(rg, g, 0, inv_r, 1.f, 1.f, sm.X[0], sm.Y[0], sm.E[0]);
+    if (nt > 1) tile_request<DA, false>(rg, g, hd, u, kTS, tok, ib, ts4, ts4, fk, nullptr, nullptr);
+    __syncthreads();
 
     f32x16 O = {0};
     float m = -INFINITY, l = 0.f;
-    for (int j0 = 0; j0 < g.N; j0 += kTS) {
-        __syncthreads();
-        tile_commit<DA, false>(rg, g, inv_r, 1.f, 1.f, sm.X, sm.Y, sm.E);
-        __syncthreads();
-        if (j0 + kTS < g.N)
-            tile_request<DA, false>(rg, g, hd, u, j0 + kTS, tok, k, g.tstride, fk, v, g.tstride, nullptr, nullptr);
+    for (int tile = 0; tile < nt; ++tile) {
+        const int cur = tile & 1, j0 = tile * kTS;
+        const float *Xc = sm.X[cur], *Yc = sm.Y[cur];
+        Pre pre;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pre.v[i] = Xc[col * XS + hf + 2 * i];
 #pragma unroll 1
         for (int kb = 0; kb < kTS / 32; ++kb) {
             const int key0 = j0 + kb * 32;
             if (key0 >= g.N) break;
-            const float *Xb = sm.X + (kb * 32 + col) * kXS + hf;
+            const float *Xb = Xc + (kb * 32 + col) * XS + hf;
+            const float *Yb = Yc + (kb * 32 + 4 * hf) * kYS + col;
             f32x16 S = {0};
-            mfma_seq<DA / 2>(S, [&](int t) { return Xb[2 * t]; }, [&](int t) { return Qr[t]; });
+            mfma_seq<DA / 2>(S, pre, [&](int t) { return Xb[2 * t]; }, [&](int t) { return Qr[t]; },
+                             [&](Pre &nx) {
+#pragma unroll
+                                 for (int i = 0; i < 8; ++i) nx.v[i] = Yb[acc_row(i) * kYS];
+                             });
             if (key0 + 32 > g.N) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (key0 + 8 * (i >> 2) + 4 * hf + (i & 3) >= g.N) S[i] = -INFINITY;
+                    if (key0 + acc_row(i) + 4 * hf >= g.N) S[i] = -INFINITY;
             }
             float mx = m;
 #pragma unroll
@@ -238,9 +269,20 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_fwd_kernel(Geo g, int nblk, u
                 O[i] *= alpha;
             }
             l = l * alpha + ps;
-            const float *Yb = sm.Y + (kb * 32 + 4 * hf) * kYS + col;
-            mfma_seq<16>(O, [&](int i) { return Yb[acc_row(i) * kYS]; }, [&](int i) { return S[i]; });
+            mfma_seq<16>(O, pre, [&](int i) { return Yb[acc_row(i) * kYS]; }, [&](int i) { return S[i]; },
+                         [&](Pre &nx) {
+                             if (kb + 1 < kTS / 32) {
+#pragma unroll
+                                 for (int i = 0; i < 8; ++i) nx.v[i] = Xb[32 * XS + 2 * i];
+                             }
+                         });
         }
+        if (tile + 1 < nt) {
+            tile_commit<DA, XS, false>(rg, g, j0 + kTS, inv_r, 1.f, 1.f, sm.X[cur ^ 1], sm.Y[cur ^ 1], sm.E[cur ^ 1]);
+            if (tile + 2 < nt)
+                tile_request<DA, false>(rg, g, hd, u, j0 + 2 * kTS, tok, ib, ts4, ts4, fk, nullptr, nullptr);
+        }
+        __syncthreads();
     }
     l += __shfl_xor(l, 32);
     if (!live) return;
@@ -250,7 +292,7 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_fwd_kernel(Geo g, int nblk, u
     float *raw = g.out_raw ? (float *)g.out_raw + base : nullptr;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int c = 8 * (i >> 2) + 4 * hf + (i & 3);
+        const int c = acc_row(i) + 4 * hf;
         if (c >= g.d) continue;
         const float o = O[i] * inv;
         if (gt) {       // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
@@ -274,7 +316,8 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dq_kernel(Geo g, int nblk, ui
                                                               float *__restrict__ dfq_part)
 {
     constexpr int RB = DA > 32 ? 2 : 1;     // 32-row blocks of dQ_aug^T
-    __shared__ Smem sm;
+    constexpr int XS = kXS;                 // all 64 columns: the second row block reads columns 32..63
+    __shared__ Smem<XS> sm;
     int64_t u;
     int blk;
     unit_of_block(nblk, u, blk);
@@ -282,8 +325,15 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dq_kernel(Geo g, int nblk, ui
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
 
     const TokMap tok = fill_tok_map<kNT>(g, w, sm.tokl);
-    zero_x_tile(sm.X);      // columns d + r .. 63 are never written: zero operands, and finite rows of dQ_aug^T beyond d + r
+    zero_x_tiles<XS>(sm.X[0]);      // zero operands beyond d + r, and finite (unused) rows of dQ_aug^T there
     __syncthreads();
+
+    const int nt = (g.N + kTS - 1) / kTS;
+    const int tok0 = (w / (g.nwx * g.nwy)) * g.H * g.W;
+    const uint32_t ts4 = (uint32_t)g.tstride * 4u;
+    const ImgBase ib = {(const char *)(k + (int64_t)tok0 * g.tstride), (const char *)(v + (int64_t)tok0 * g.tstride), tok0};
+    TileRegs<DA> rg;
+    tile_request<DA, false>(rg, g, hd, u, 0, tok, ib, ts4, ts4, fk, nullptr, nullptr);
 
     const int qi = blk * kRowsWg + wave * 32 + col;
     const bool live = qi < g.N;
@@ -300,8 +350,9 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dq_kernel(Geo g, int nblk, ui
     }
     const float lse2 = lse[u * g.N + qc] * kLog2e, dl = delta[u * g.N + qc];
 
-    TileRegs<DA> rg;
-    tile_request<DA, false>(rg, g, hd, u, 0, tok, k, g.tstride, fk, v, g.tstride, nullptr, nullptr);
+    tile_commit<DA, XS, false>(rg, g, 0, inv_r, 1.f, 1.f, sm.X[0], sm.Y[0], sm.E[0]);
+    if (nt > 1) tile_request<DA, false>(rg, g, hd, u, kTS, tok, ib, ts4, ts4, fk, nullptr, nullptr);
+    __syncthreads();
 
     f32x16 acc[RB];
 #pragma unroll
@@ -309,29 +360,52 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dq_kernel(Geo g, int nblk, ui
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 
-    for (int j0 = 0; j0 < g.N; j0 += kTS) {
-        __syncthreads();
-        tile_commit<DA, false>(rg, g, inv_r, 1.f, 1.f, sm.X, sm.Y, sm.E);
-        __syncthreads();
-        if (j0 + kTS < g.N)
-            tile_request<DA, false>(rg, g, hd, u, j0 + kTS, tok, k, g.tstride, fk, v, g.tstride, nullptr, nullptr);
+    for (int tile = 0; tile < nt; ++tile) {
+        const int cur = tile & 1, j0 = tile * kTS;
+        const float *Xc = sm.X[cur], *Yc = sm.Y[cur];
+        Pre pre;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pre.v[i] = Xc[col * XS + hf + 2 * i];
 #pragma unroll 1
         for (int kb = 0; kb < kTS / 32; ++kb) {
             if (j0 + kb * 32 >= g.N) break;
             // keys >= N are zero rows: their dS is finite and meets a zero K_aug row
-            const float *Xb = sm.X + (kb * 32 + col) * kXS + hf;
-            const float *Yb = sm.Y + (kb * 32 + col) * kYS + hf;
+            const float *Xb = Xc + (kb * 32 + col) * XS + hf;
+            const float *Yb = Yc + (kb * 32 + col) * kYS + hf;
+            const float *Xt = Xc + (kb * 32 + 4 * hf) * XS + col;
             f32x16 S = {0}, D = {0};
-            mfma_seq<DA / 2>(S, [&](int t) { return Xb[2 * t]; }, [&](int t) { return Qr[t]; });
-            mfma_seq<16>(D, [&](int t) { return Yb[2 * t]; }, [&](int t) { return Gr[t]; });
+            mfma_seq<DA / 2>(S, pre, [&](int t) { return Xb[2 * t]; }, [&](int t) { return Qr[t]; },
+                             [&](Pre &nx) {
+#pragma unroll
+                                 for (int i = 0; i < 8; ++i) nx.v[i] = Yb[2 * i];
+                             });
+            mfma_seq<16>(D, pre, [&](int t) { return Yb[2 * t]; }, [&](int t) { return Gr[t]; },
+                         [&](Pre &nx) {
+#pragma unroll
+                             for (int i = 0; i < 8; ++i) nx.v[i] = Xt[acc_row(i) * XS];
+                         });
 #pragma unroll
             for (int i = 0; i < 16; ++i) S[i] = __builtin_amdgcn_exp2f(S[i] - lse2) * (D[i] - dl);
 #pragma unroll
             for (int b = 0; b < RB; ++b) {
-                const float *Xt = sm.X + (kb * 32 + 4 * hf) * kXS + 32 * b + col;
-                mfma_seq<16>(acc[b], [&](int i) { return Xt[acc_row(i) * kXS]; }, [&](int i) { return S[i]; });
+                mfma_seq<16>(acc[b], pre, [&](int i) { return Xt[acc_row(i) * XS + 32 * b]; }, [&](int i) { return S[i]; },
+                             [&](Pre &nx) {
+                                 if (b + 1 < RB) {
+#pragma unroll
+                                     for (int i = 0; i < 8; ++i) nx.v[i] = Xt[acc_row(i) * XS + 32 * (b + 1)];
+                                 } else if (kb + 1 < kTS / 32) {
+#pragma unroll
+                                     for (int i = 0; i < 8; ++i) nx.v[i] = Xb[32 * XS + 2 * i];
+                                 }
+                             });
             }
         }
+        if (tile + 1 < nt) {
+            tile_commit<DA, XS, false>(rg, g, j0 + kTS, inv_r, 1.f, 1.f, sm.X[cur ^ 1], sm.Y[cur ^ 1], sm.E[cur ^ 1]);
+            if (tile + 2 < nt)
+                tile_request<DA, false>(rg, g, hd, u, j0 + 2 * kTS, tok, ib, ts4, ts4, fk, nullptr, nullptr);
+        }
+        __syncthreads();
     }
     if (!live) return;
     float *dst = dq + (int64_t)tq * g.C + hd * g.d;
@@ -340,7 +414,7 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dq_kernel(Geo g, int nblk, ui
     for (int b = 0; b < RB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int c = 32 * b + 8 * (i >> 2) + 4 * hf + (i & 3);
+            const int c = 32 * b + acc_row(i) + 4 * hf;
             if (c < g.d) dst[c] = acc[b][i] * g.scale_c;
             else if (c < g.d + g.r) fdst[c - g.d] = acc[b][i] * g.scale_p;
         }
@@ -359,7 +433,8 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dkv_kernel(Geo g, int nblk, u
                                                                float *__restrict__ dv, float *__restrict__ dfk_part)
 {
     constexpr int RB = DA > 32 ? 2 : 1;
-    __shared__ Smem sm;
+    constexpr int XS = kXS;
+    __shared__ Smem<XS> sm;
     int64_t u;
     int blk;
     unit_of_block(nblk, u, blk);
@@ -367,8 +442,15 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dkv_kernel(Geo g, int nblk, u
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
 
     const TokMap tok = fill_tok_map<kNT>(g, w, sm.tokl);
-    zero_x_tile(sm.X);
+    zero_x_tiles<XS>(sm.X[0]);
     __syncthreads();
+
+    const int nt = (g.N + kTS - 1) / kTS;
+    const int tok0 = (w / (g.nwx * g.nwy)) * g.H * g.W;
+    const uint32_t ts4 = (uint32_t)g.tstride * 4u;
+    const ImgBase ib = {(const char *)(q + (int64_t)tok0 * g.tstride), (const char *)(dout + (int64_t)tok0 * g.C), tok0};
+    TileRegs<DA> rg;
+    tile_request<DA, true>(rg, g, hd, u, 0, tok, ib, ts4, (uint32_t)g.C * 4u, fq, lse, delta);
 
     const int ki = blk * kRowsWg + wave * 32 + col;
     const bool live = ki < g.N;
@@ -383,8 +465,9 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dkv_kernel(Geo g, int nblk, u
         Vr[t] = c < g.d ? v[(int64_t)tk * g.tstride + hd * g.d + c] : 0.f;
     }
 
-    TileRegs<DA> rg;
-    tile_request<DA, true>(rg, g, hd, u, 0, tok, q, g.tstride, fq, dout, (int64_t)g.C, lse, delta);
+    tile_commit<DA, XS, true>(rg, g, 0, inv_r, g.scale_c, g.scale_p, sm.X[0], sm.Y[0], sm.E[0]);
+    if (nt > 1) tile_request<DA, true>(rg, g, hd, u, kTS, tok, ib, ts4, (uint32_t)g.C * 4u, fq, lse, delta);
+    __syncthreads();
 
     f32x16 dKa[RB], dVa = {0};
 #pragma unroll
@@ -392,23 +475,33 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dkv_kernel(Geo g, int nblk, u
 #pragma unroll
         for (int i = 0; i < 16; ++i) dKa[b][i] = 0.f;
 
-    for (int i0 = 0; i0 < g.N; i0 += kTS) {
-        __syncthreads();
-        tile_commit<DA, true>(rg, g, inv_r, g.scale_c, g.scale_p, sm.X, sm.Y, sm.E);
-        __syncthreads();
-        if (i0 + kTS < g.N)
-            tile_request<DA, true>(rg, g, hd, u, i0 + kTS, tok, q, g.tstride, fq, dout, (int64_t)g.C, lse, delta);
+    for (int tile = 0; tile < nt; ++tile) {
+        const int cur = tile & 1, i0 = tile * kTS;
+        const float *Xc = sm.X[cur], *Yc = sm.Y[cur], *Ec = sm.E[cur];
+        Pre pre;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) pre.v[i] = Xc[col * XS + hf + 2 * i];
 #pragma unroll 1
         for (int qb = 0; qb < kTS / 32; ++qb) {
             if (i0 + qb * 32 >= g.N) break;
             // queries >= N are zero rows with LSE = delta = 0: P = 1, dS = 0, and both meet zero rows
-            const float *Xb = sm.X + (qb * 32 + col) * kXS + hf;
-            const float *Yb = sm.Y + (qb * 32 + col) * kYS + hf;
+            const float *Xb = Xc + (qb * 32 + col) * XS + hf;
+            const float *Yb = Yc + (qb * 32 + col) * kYS + hf;
+            const float *Yt = Yc + (qb * 32 + 4 * hf) * kYS + col;
+            const float *Xt = Xc + (qb * 32 + 4 * hf) * XS + col;
             f32x16 S = {0}, D = {0};
-            mfma_seq<DA / 2>(S, [&](int t) { return Xb[2 * t]; }, [&](int t) { return Kr[t]; });
-            mfma_seq<16>(D, [&](int t) { return Yb[2 * t]; }, [&](int t) { return Vr[t]; });
+            mfma_seq<DA / 2>(S, pre, [&](int t) { return Xb[2 * t]; }, [&](int t) { return Kr[t]; },
+                             [&](Pre &nx) {
+#pragma unroll
+                                 for (int i = 0; i < 8; ++i) nx.v[i] = Yb[2 * i];
+                             });
+            mfma_seq<16>(D, pre, [&](int t) { return Yb[2 * t]; }, [&](int t) { return Vr[t]; },
+                         [&](Pre &nx) {
+#pragma unroll
+                             for (int i = 0; i < 8; ++i) nx.v[i] = Yt[acc_row(i) * kYS];
+                         });
             // rows of S are queries: register 4j + i belongs to query 8j + 4hf + i of the block
-            const float *Le = sm.E + qb * 32 + 4 * hf, *De = sm.E + 64 + qb * 32 + 4 * hf;
+            const float *Le = Ec + qb * 32 + 4 * hf, *De = Ec + 64 + qb * 32 + 4 * hf;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 const int rq = acc_row(i);
@@ -416,14 +509,31 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dkv_kernel(Geo g, int nblk, u
                 S[i] = p;
                 D[i] = p * (D[i] - De[rq]);
             }
-            const float *Yt = sm.Y + (qb * 32 + 4 * hf) * kYS + col;
-            mfma_seq<16>(dVa, [&](int i) { return Yt[acc_row(i) * kYS]; }, [&](int i) { return S[i]; });
+            mfma_seq<16>(dVa, pre, [&](int i) { return Yt[acc_row(i) * kYS]; }, [&](int i) { return S[i]; },
+                         [&](Pre &nx) {
+#pragma unroll
+                             for (int i = 0; i < 8; ++i) nx.v[i] = Xt[acc_row(i) * XS];
+                         });
 #pragma unroll
             for (int b = 0; b < RB; ++b) {
-                const float *Xt = sm.X + (qb * 32 + 4 * hf) * kXS + 32 * b + col;
-                mfma_seq<16>(dKa[b], [&](int i) { return Xt[acc_row(i) * kXS]; }, [&](int i) { return D[i]; });
+                mfma_seq<16>(dKa[b], pre, [&](int i) { return Xt[acc_row(i) * XS + 32 * b]; }, [&](int i) { return D[i]; },
+                             [&](Pre &nx) {
+                                 if (b + 1 < RB) {
+#pragma unroll
+                                     for (int i = 0; i < 8; ++i) nx.v[i] = Xt[acc_row(i) * XS + 32 * (b + 1)];
+                                 } else if (qb + 1 < kTS / 32) {
+#pragma unroll
+                                     for (int i = 0; i < 8; ++i) nx.v[i] = Xb[32 * XS + 2 * i];
+                                 }
+                             });
             }
         }
+        if (tile + 1 < nt) {
+            tile_commit<DA, XS, true>(rg, g, i0 + kTS, inv_r, g.scale_c, g.scale_p, sm.X[cur ^ 1], sm.Y[cur ^ 1], sm.E[cur ^ 1]);
+            if (tile + 2 < nt)
+                tile_request<DA, true>(rg, g, hd, u, i0 + 2 * kTS, tok, ib, ts4, (uint32_t)g.C * 4u, fq, lse, delta);
+        }
+        __syncthreads();
     }
     if (!live) return;
     float *kdst = dk + (int64_t)tk * g.C + hd * g.d;
@@ -431,14 +541,14 @@ __global__ __launch_bounds__(kNT, 2) void mfma_f32_dkv_kernel(Geo g, int nblk, u
     float *fdst = dfk_part + (u * g.N + ki) * g.r;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int c = 8 * (i >> 2) + 4 * hf + (i & 3);
+        const int c = acc_row(i) + 4 * hf;
         if (c < g.d) vdst[c] = dVa[i];
     }
 #pragma unroll
     for (int b = 0; b < RB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            const int c = 32 * b + 8 * (i >> 2) + 4 * hf + (i & 3);
+            const int c = 32 * b + acc_row(i) + 4 * hf;
             if (c < g.d) kdst[c] = dKa[b][i];
             else if (c < g.d + g.r) fdst[c - g.d] = dKa[b][i];
         }
@@ -482,8 +592,9 @@ hipError_t bwd_t(const Geo &g, const void *q, const void *k, const void *v, cons
 // enough to fill a 32-token block; everything else stays on the vector-ALU kernels.
 bool mfma_f32_supported(const Geo &g, int dtype)
 {
+    const int64_t image_bytes = (int64_t)g.H * g.W * (g.tstride > g.C ? g.tstride : (int64_t)g.C) * 4;
     return dtype == RIB_F32 && !(g.flags & RIB_FLAG_VECTOR_ONLY) && g.d <= 32 && g.d + g.r <= 64 && g.N >= 32 &&
-           g.M <= 256;
+           g.M <= 256 && image_bytes < ((int64_t)1 << 32);
 }
 
 hipError_t launch_mfma_f32_fwd(const Geo &g, const void *q, const void *k, const void *v, const void *fq,

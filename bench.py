@@ -24,6 +24,7 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, vendor figure
 PEAK_F32_VALU_TFLOPS = 157.3  # MI355X fp32 vector, vendor figure
+PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 MFMA, vendor figure
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
 # plain copy of known size (profiles/c5_step_hbm_traffic.md); only for the workload it was measured on.
@@ -43,6 +44,15 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-units", type=int, default=0, help="units in the CPU-oracle sample (0 = auto)")
     return ap.parse_args()
+
+
+def family_peak(family):
+    """(published peak in TFLOP/s, roofline bound) of a kernel family."""
+    if family == "mfma-bf16":
+        return PEAK_BF16_TFLOPS, "mfma"
+    if family == "mfma-f32":
+        return PEAK_F32_MFMA_TFLOPS, "mfma"
+    return PEAK_F32_VALU_TFLOPS, "alu"
 
 
 class Runner:
@@ -246,19 +256,19 @@ def main():
                    bwd_pct_bf16_peak=round(100 * bwd_tflops / PEAK_BF16_TFLOPS, 2),
                    bwd_ms_median=r.last_stats["bwd_ms_median"], bwd_ms_min=r.last_stats["bwd_ms_min"])
     # roofline of the forward kernel (one launch per step; algorithmic flop of the unpadded dims)
-    mfma = rb.kernel_name(r.p, False) == "mfma-bf16"
-    peak = PEAK_BF16_TFLOPS if mfma else PEAK_F32_VALU_TFLOPS
-    res["roofline"] = {"kernel": "forward (" + rb.kernel_name(r.p, False) + ")",
-                       "bound": "mfma" if mfma else "alu", "achieved": round(fwd_tflops, 2), "peak": peak,
+    fam = rb.kernel_name(r.p, False)
+    mfma = fam == "mfma-bf16"
+    peak, bound = family_peak(fam)
+    res["roofline"] = {"kernel": "forward (" + fam + ")",
+                       "bound": bound, "achieved": round(fwd_tflops, 2), "peak": peak,
                        "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4),
                        "traffic": MEASURED_FWD_TRAFFIC.get(wl.name),
                        "algorithmic_flop": wl.fwd_flop, "algorithmic_bytes": wl.fwd_bytes,
                        "issue_ceiling_tflops": 1318.0 if mfma and wl.d == 30 and wl.r == 16 else None}
     if wl.backward:
-        bmfma = rb.kernel_name(r.p, True) == "mfma-bf16"
-        bpeak = PEAK_BF16_TFLOPS if bmfma else PEAK_F32_VALU_TFLOPS
+        bpeak, bbound = family_peak(rb.kernel_name(r.p, True))
         res["roofline_bwd"] = {"kernel": "backward (" + rb.kernel_name(r.p, True) + ", all its launches)",
-                               "bound": "mfma" if bmfma else "alu", "achieved": round(bwd_tflops, 2),
+                               "bound": bbound, "achieved": round(bwd_tflops, 2),
                                "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4),
                                "traffic": MEASURED_BWD_TRAFFIC.get(wl.name), "algorithmic_flop": wl.bwd_flop}
     del r
@@ -270,7 +280,7 @@ def main():
             r2 = Runner(w2.__class__(**{**w2.__dict__, "backward": False}), flags)
             _, f_ms, _ = time_steps(r2, min(50, max(10, a.steps)), min(a.warmup, 10))
             tf = w2.fwd_flop / (f_ms * 1e-3) / 1e12
-            pk = PEAK_BF16_TFLOPS if rb.kernel_name(r2.p, False) == "mfma-bf16" else PEAK_F32_VALU_TFLOPS
+            pk = family_peak(rb.kernel_name(r2.p, False))[0]
             table[name] = {"fwd_ms": round(f_ms, 4), "fwd_tflops": round(tf, 2),
                            "tokens_per_s": round(w2.tokens / (f_ms * 1e-3), 1),
                            "frac_of_peak": round(tf / pk, 4), "peak_tflops": pk,
@@ -304,6 +314,23 @@ def main():
         res["sst_plus_block"] = {"layers": stack, "fwd_ms": round(f_ms, 4), "bwd_ms": round(b_ms, 4),
                                  "tflops": round(flop / ((f_ms + b_ms) * 1e-3) / 1e12, 1),
                                  "tokens_per_s": round(wk.SCHEDULE[stack[0]].tokens / ((f_ms + b_ms) * 1e-3), 1)}
+        # the same shapes in fp32 storage (the paper quotes its costs at FP32): fp32 MFMA kernels, fp32 peak
+        f32 = {}
+        for name in ("c2", "c3", "c4", "c5"):
+            w2 = wk.WORKLOADS[name]
+            w2 = w2.__class__(**{**w2.__dict__, "dtype": "f32", "name": name + "-f32"})
+            r2 = Runner(w2, flags)
+            _, f_ms, b_ms = time_steps(r2, 10, 3)
+            pk = family_peak(rb.kernel_name(r2.p, False))[0]
+            ftf = w2.fwd_flop / (f_ms * 1e-3) / 1e12
+            f32[w2.name] = {"fwd_ms": round(f_ms, 4), "fwd_tflops": round(ftf, 1), "frac_of_peak": round(ftf / pk, 4),
+                            "peak_tflops": pk, "kernel": rb.kernel_name(r2.p, False)}
+            if w2.backward:
+                btf = w2.bwd_flop / (b_ms * 1e-3) / 1e12
+                f32[w2.name].update(bwd_ms=round(b_ms, 4), bwd_tflops=round(btf, 1), bwd_frac_of_peak=round(btf / pk, 4))
+            del r2
+            torch.cuda.empty_cache()
+        res["configs_f32"] = f32
         res["generator"] = time_generator(rb, torch)
         res["gated_c5"] = time_gated(rb, torch, wk.WORKLOADS["c5"])
 

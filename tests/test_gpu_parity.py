@@ -374,7 +374,7 @@ def test_f32_matrix_core_kernels(oracle, gh, wl):
 
 
 def test_f32_training_shape_sampled_units(oracle, gh):
-    """Config 5's shape in fp32 storage (the paper trains in fp32), full size: forward on sampled
+    """Config 5's shape in fp32 storage (the paper quotes its costs at FP32), full size: forward on sampled
     units, backward on every element (the RIB gradients sum 144 windows), and a rerun of the
     backward must reproduce the first run bit for bit (fixed summation order)."""
     from dataclasses import replace

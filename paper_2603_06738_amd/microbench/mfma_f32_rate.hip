@@ -1,6 +1,8 @@
 // Micro-benchmark: sustained rate of v_mfma_f32_32x32x2_f32 (the fp32 matrix instruction the fp32
 // kernels are built on), registers only, with constant and with random operands, one to three
-// waves per SIMD, accumulating into one register block or into two alternately.
+// waves per SIMD, accumulating into one register block or into two alternately; and whether
+// independent vector instructions (v_fma_f32, v_exp_f32) issued between the MFMAs ride along for
+// free, as they do beside the bf16 MFMAs, or add their own time.
 //   hipcc --offload-arch=gfx950 -O3 -Xclang -target-feature -Xclang -packed-fp32-ops -o mfma_f32_rate mfma_f32_rate.hip && ./mfma_f32_rate
 #include <hip/hip_runtime.h>
 #include <cstdio>
@@ -29,6 +31,30 @@ __global__ __launch_bounds__(256) void rate(float* out, int iters)
     for (int n = 0; n < NACC; ++n) for (int i = 0; i < 16; ++i) t += c[n][i];
     out[blockIdx.x * blockDim.x + threadIdx.x] = t;
 }
+// VAL independent vector instructions after every MFMA (EXP: v_exp_f32, else v_fma_f32)
+template <int VAL, bool EXP>
+__global__ __launch_bounds__(256) void mix(float* out, int iters)
+{
+    float a = threadIdx.x * 0.001f, b = 0.5f, x[8];
+    for (int i = 0; i < 8; ++i) x[i] = threadIdx.x * 1e-4f + i;
+    f32x16 c;
+    for (int i = 0; i < 16; ++i) c[i] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            MF(c, a, b);
+#pragma unroll
+            for (int v = 0; v < VAL; ++v) {
+                if (EXP) asm volatile("v_exp_f32 %0, %1" : "=v"(x[(i * VAL + v) % 8]) : "v"(x[(i * VAL + v) % 8]));
+                else asm volatile("v_fma_f32 %0, %1, %1, %0" : "+v"(x[(i * VAL + v) % 8]) : "v"(b));
+            }
+        }
+    }
+    float t = 0;
+    for (int i = 0; i < 16; ++i) t += c[i];
+    for (int i = 0; i < 8; ++i) t += x[i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = t;
+}
 template <typename F> static float best_ms(F f)
 {
     hipEvent_t e0, e1; hipEventCreate(&e0); hipEventCreate(&e1);
@@ -55,6 +81,10 @@ int main()
         line("2 accumulators, constant operands", best_ms([&] { rate<2, false><<<blocks, 256>>>(out, iters); }));
         line("1 accumulator, random operands", best_ms([&] { rate<1, true><<<blocks, 256>>>(out, iters); }));
         line("2 accumulators, random operands", best_ms([&] { rate<2, true><<<blocks, 256>>>(out, iters); }));
+        line("+ 4 v_fma_f32 per MFMA", best_ms([&] { mix<4, false><<<blocks, 256>>>(out, iters); }));
+        line("+ 8 v_fma_f32 per MFMA", best_ms([&] { mix<8, false><<<blocks, 256>>>(out, iters); }));
+        line("+ 2 v_exp_f32 per MFMA", best_ms([&] { mix<2, true><<<blocks, 256>>>(out, iters); }));
+        line("+ 4 v_exp_f32 per MFMA", best_ms([&] { mix<4, true><<<blocks, 256>>>(out, iters); }));
     }
     CK(hipDeviceSynchronize());
     return 0;

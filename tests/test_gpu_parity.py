@@ -194,14 +194,15 @@ def test_paper_schedule_layers(oracle, gh, name):
 
 
 GATED = [
-    wk.custom("gate-f32", "f32", 1, 16, 16, 2, 30, 16, 16, 3, 231, backward=True),          # vector-ALU kernels
+    wk.custom("gate-f32", "f32", 1, 16, 16, 2, 30, 16, 16, 3, 231, backward=True),          # fp32 matrix-core kernels
+    wk.custom("gate-f32-m9", "f32", 1, 9, 18, 2, 30, 8, 9, 3, 235, backward=True),          # the same, ragged window
     wk.custom("gate-m12", "bf16", 1, 24, 12, 2, 30, 16, 12, 7, 232, backward=True),         # general matrix-core kernels
     wk.custom("gate-m32", "bf16", 2, 32, 64, 3, 30, 18, 32, 16, 233, backward=True),        # fast kernels
     wk.custom("gate-d32", "bf16", 1, 16, 32, 2, 32, 32, 16, 0, 234, backward=True),
 ]
 
 
-@pytest.mark.parametrize("flags", [0, rb.RIB_FLAG_WIDE], ids=["default", "wide"])
+@pytest.mark.parametrize("flags", [0, rb.RIB_FLAG_WIDE, rb.RIB_FLAG_VECTOR_ONLY], ids=["default", "wide", "vector"])
 @pytest.mark.parametrize("wl", GATED, ids=lambda w: w.name)
 def test_gated_forward_and_backward(oracle, gh, wl, flags):
     """CLA gate (Eq. 9) fused into the epilogue, and the gated backward (dO = dO' * G and

@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="c5")
+    ap.add_argument("--dtype", choices=["bf16", "f32"], default=None,
+                    help="run the workload in this storage type instead of its own (fp32: the fp32 MFMA kernels)")
     ap.add_argument("--all", action="store_true", help="also time the forward of every named workload")
     ap.add_argument("--force-row-max", action="store_true", help="time the max-tracking softmax path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -227,6 +229,8 @@ def main():
         sys.exit(1)
     rb.load()
     wl = {**wk.WORKLOADS, **wk.SCHEDULE}[a.workload]
+    if a.dtype and a.dtype != wl.dtype:
+        wl = wl.__class__(**{**wl.__dict__, "dtype": a.dtype, "name": wl.name + "-" + a.dtype})
     flags = rb.RIB_FLAG_FORCE_ROW_MAX if a.force_row_max else 0
 
     r = Runner(wl, flags)

@@ -221,8 +221,10 @@ rib_status rib_features_bwd(const rib_gen_params *p, const float *W_h, const flo
 /* Static, NUL-terminated description of a status code. */
 const char *rib_status_string(rib_status st);
 
-/* Name of the kernel family that would serve this problem ("mfma-bf16",
- * "valu-f32", ...), or NULL if the parameters are invalid.  For logs and tests. */
+/* Name of the kernel family that would serve this problem: "mfma-bf16" (bf16
+ * storage on the bf16 matrix instructions), "mfma-f32" (fp32 storage on the
+ * fp32 matrix instruction) or "valu-f32" (vector ALU, any storage); NULL if the
+ * parameters are invalid.  For logs and tests. */
 const char *rib_window_attn_kernel_name(const rib_params *p, int backward);
 
 #ifdef __cplusplus

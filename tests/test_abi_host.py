@@ -151,3 +151,28 @@ def test_gated_entry_points_validate():
         a[i] = None
         assert rb.rib_window_attn_gated_bwd_status(p, *a, 0x1000, need, stream=0) == 1, i
     assert rb.rib_window_attn_gated_bwd_workspace_bytes(good(shift=9)) == 0
+
+
+def test_kernel_family_selection_is_host_logic():
+    """Which family serves a problem is decided on the host (no GPU needed): matrix-core kernels
+    for d <= 32 and d + r <= 64 (bf16: even d and r, 64+ tokens; fp32: 32+ tokens), the vector ALU
+    for everything else and for anything under RIB_FLAG_VECTOR_ONLY."""
+    def name(back=False, **kw):
+        base = dict(B=1, H=16, W=16, heads=2, d=30, r=16, window=16, shift=0, scale_c=0.1, scale_p=0.1, dtype="bf16")
+        base.update(kw)
+        return rb.kernel_name(rb.make_params(**base), backward=back)
+    for back in (False, True):
+        assert name(back) == "mfma-bf16"
+        assert name(back, dtype="f32") == "mfma-f32"
+        assert name(back, flags=rb.RIB_FLAG_VECTOR_ONLY) == "valu-f32"
+        assert name(back, dtype="f32", flags=rb.RIB_FLAG_VECTOR_ONLY) == "valu-f32"
+        assert name(back, d=40, r=8) == "valu-f32"                          # d > 32
+        assert name(back, d=32, r=34) == "valu-f32"                         # d + r > 64
+        assert name(back, d=32, r=34, dtype="f32") == "valu-f32"
+        assert name(back, d=31, r=33, dtype="f32") == "mfma-f32"            # odd d and r are fine in fp32
+        assert name(back, d=31, r=16) == "valu-f32"                         # ... not in bf16 (pairs of channels)
+        assert name(back, H=5, W=5, window=5, dtype="f32") == "valu-f32"    # 25 tokens: below one 32-token block
+        assert name(back, H=6, W=6, window=6, dtype="f32") == "mfma-f32"    # 36 tokens
+        assert name(back, H=6, W=6, window=6) == "valu-f32"                 # bf16 kernels start at 64 tokens
+    # offsets inside one image must fit 32 bits for the fp32 matrix-core kernels
+    assert name(dtype="f32", H=8192, W=8192, heads=1, d=32, r=0, window=16) == "valu-f32"

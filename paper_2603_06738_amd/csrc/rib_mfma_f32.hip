@@ -4,8 +4,10 @@
 // throughout: operands, products, accumulators and the softmax state are fp32, so the result
 // meets the fp32 tolerance.  The vector-ALU kernels need one LDS operand per multiply-add
 // and reach about a seventh of the fp32 peak; the fp32 MFMA has the same peak as the vector
-// ALU but takes its operands once per 2048 multiply-adds, which leaves these kernels
-// matrix-pipe bound.
+// ALU but takes its operands once per 2048 multiply-adds.  It does occupy the vector ALU while
+// it runs (measured: vector instructions between fp32 MFMAs add their full time, with one,
+// two or three waves per SIMD), so a block costs its MFMA time plus its vector-instruction
+// time, and everything around the MFMA chains is kept short.
 //
 // Layout of v_mfma_f32_32x32x2_f32 (D = A[32x2] * B[2x32] + C): lane l supplies
 // A[l % 32][l / 32] and B[l / 32][l % 32] and holds D[8j + 4(l / 32) + i][l % 32] in register
@@ -18,7 +20,8 @@
 //
 // One workgroup = 4 waves = 128 consecutive window-local tokens of one (window, head) unit
 // kept in registers; the other side is streamed through LDS in tiles of 64 tokens, fetched
-// one tile ahead into registers.  Any window size, any d <= 32, d + r <= 64.
+// one tile ahead into registers, two LDS stages, one workgroup barrier per tile.  Any window of
+// 32 or more tokens, any d <= 32, d + r <= 64.
 #include "rib_common.h"
 
 namespace rib {

@@ -2,12 +2,16 @@
 // kernel-family selection and launches.  Nothing here allocates device memory or
 // synchronises.
 #include <cmath>
+#include <mutex>
+#include <set>
+#include <utility>
 
 #include "rib_common.h"
 
 namespace rib {
 namespace {
 
+constexpr int kMaxDevices = 64;
 // Validate everything that does not involve data pointers and fill Geo.
 rib_status make_geo(const rib_params *p, Geo *g)
 {
@@ -43,7 +47,65 @@ rib_status make_geo(const rib_params *p, Geo *g)
     return RIB_OK;
 }
 
+rib_status check_bwd(const rib_params *p, Geo *g, const void *q, const void *k, const void *v, const void *f_q,
+                     const void *f_k, const void *out, const void *d_out, const float *lse, void *dq, void *dk,
+                     void *dv, float *df_q, float *df_k)
+{
+    rib_status st = make_geo(p, g);
+    if (st != RIB_OK) return st;
+    if (!q || !k || !v || !out || !d_out || !lse || !dq || !dk || !dv) return RIB_ERR_NULL;
+    if (g->r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
+    return RIB_OK;
+}
+
+// The plain backward on whichever kernel family serves the problem; `ws` holds bwd_ws_layout(g).total bytes.
+rib_status enqueue_bwd(const Geo &g, int dtype, const void *q, const void *k, const void *v, const void *f_q,
+                       const void *f_k, const void *out, const void *d_out, const float *lse, void *dq, void *dk,
+                       void *dv, float *df_q, float *df_k, void *ws, hipStream_t stream)
+{
+    hipError_t e;
+    if (mfma_bwd_supported(g, dtype))
+        e = launch_mfma_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, ws, stream);
+    else if (mfma_f32_supported(g, dtype))
+        e = launch_mfma_f32_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, ws, stream);
+    else
+        e = launch_valu_bwd(g, dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, ws, stream);
+    return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
+}
+
 }  // namespace
+}  // namespace rib
+
+namespace rib {
+
+hipError_t prepare_kernel(const void *kern, int *cus)
+{
+    static std::mutex mu;
+    static std::set<std::pair<const void *, int>> raised;      // (kernel, device) pairs whose limit is set
+    static int cu_count[kMaxDevices];                          // 0 = not looked up yet
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (cus != nullptr) {
+        if (cu_count[dev] == 0) {
+            int n = 0;
+            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e != hipSuccess) return e;
+            cu_count[dev] = n;
+        }
+        *cus = cu_count[dev];
+    }
+    const auto key = std::make_pair(kern, dev);
+    if (raised.find(key) == raised.end()) {
+        e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
+        if (e != hipSuccess) return e;
+        raised.insert(key);
+    }
+    return hipSuccess;
+}
+
 }  // namespace rib
 
 using namespace rib;
@@ -165,23 +227,12 @@ rib_status rib_window_attn_bwd(const rib_params *p, const void *q, const void *k
                                void *stream)
 {
     Geo g;
-    rib_status st = make_geo(p, &g);
+    rib_status st = check_bwd(p, &g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k);
     if (st != RIB_OK) return st;
-    if (!q || !k || !v || !out || !d_out || !lse || !dq || !dk || !dv) return RIB_ERR_NULL;
-    if (g.r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < valu_bwd_workspace(g))
         return RIB_ERR_WORKSPACE;
-    hipError_t e;
-    if (mfma_bwd_supported(g, p->dtype))
-        e = launch_mfma_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
-                            (hipStream_t)stream);
-    else if (mfma_f32_supported(g, p->dtype))
-        e = launch_mfma_f32_bwd(g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
-                                (hipStream_t)stream);
-    else
-        e = launch_valu_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
-                            (hipStream_t)stream);
-    return e == hipSuccess ? RIB_OK : RIB_ERR_LAUNCH;
+    return enqueue_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
+                       (hipStream_t)stream);
 }
 
 }  // extern "C"

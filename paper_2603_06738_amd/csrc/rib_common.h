@@ -136,6 +136,12 @@ __device__ __forceinline__ TokMap fill_tok_map(const Geo &g, int w, int *lds)
     return m;
 }
 
+// Before a launch of a kernel that uses dynamic LDS: raises the kernel's dynamic-LDS limit to
+// kMaxDynLds on the CURRENT device, once per (kernel, device); a failure is returned and not
+// remembered, so a later call tries again.  If `cus` is given it receives the number of compute
+// units of the current device (looked up once per device).  Thread-safe.
+hipError_t prepare_kernel(const void *kern, int *cus);
+
 // Launchers (each returns the hipError_t of its launches).
 hipError_t launch_valu_fwd(const Geo &g, int dtype, const void *q, const void *k, const void *v,
                            const void *fq, const void *fk, void *out, float *lse, hipStream_t st);

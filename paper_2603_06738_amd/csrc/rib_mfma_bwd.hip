@@ -23,7 +23,6 @@
 //   The last r columns of dQ_aug / dK_aug are this unit's contribution to dF_q /
 //   dF_k (Sec. 3.1: the RIB features are shared by all windows); they go to a
 //   per-unit fp32 scratch and are summed over windows in a fixed order afterwards.
-#include <mutex>
 
 #include "rib_common.h"
 
@@ -1087,14 +1086,9 @@ hipError_t launch_fast(const Geo &g, const void *q, const void *k, const void *v
     if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
     auto kdkv = mfma_bwd_dkv_fast_kernel<DQK, DVK, T, WAVES, XC>;
     auto kdq = mfma_bwd_dq_fast_kernel<DQK, DVK, T, WAVES, XC>;
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [kdkv, kdq] {
-        attr_err = hipFuncSetAttribute((const void *)kdkv, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute((const void *)kdq, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
-    });
-    if (attr_err != hipSuccess) return attr_err;
+    hipError_t pe = prepare_kernel((const void *)kdkv, nullptr);
+    if (pe == hipSuccess) pe = prepare_kernel((const void *)kdq, nullptr);
+    if (pe != hipSuccess) return pe;
     const int nblk = g.N / (WAVES * 64);
     const dim3 grid((unsigned)(g.units * nblk)), block(WAVES * 64);
     hipLaunchKernelGGL(kdkv, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
@@ -1139,16 +1133,9 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     const int nblk = (ntiles + kWaves - 1) / kWaves;
     const size_t smem = (size_t)2 * L::STAGE * sizeof(bf16_t) + (size_t)ntiles * kT * sizeof(int);
     if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
-    static std::once_flag once;
-    static hipError_t attr_err = hipSuccess;
-    std::call_once(once, [] {
-        attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dq_kernel<DQK, DVK>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
-        if (attr_err == hipSuccess)
-            attr_err = hipFuncSetAttribute((const void *)mfma_bwd_dkv_kernel<DQK, DVK>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynLds);
-    });
-    if (attr_err != hipSuccess) return attr_err;
+    hipError_t pe = prepare_kernel((const void *)mfma_bwd_dq_kernel<DQK, DVK>, nullptr);
+    if (pe == hipSuccess) pe = prepare_kernel((const void *)mfma_bwd_dkv_kernel<DQK, DVK>, nullptr);
+    if (pe != hipSuccess) return pe;
     const dim3 grid((unsigned)(g.units * nblk)), block(kNT);
     hipLaunchKernelGGL((mfma_bwd_dkv_kernel<DQK, DVK>), grid, block, smem, st, g, nblk, (const bf16_t *)q,
                        (const bf16_t *)k, (const bf16_t *)v, (const bf16_t *)fq, (const bf16_t *)fk,

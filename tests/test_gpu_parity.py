@@ -114,8 +114,8 @@ def test_large_logits_need_the_row_max(oracle, gh):
 
     Bounds.  fp32 storage keeps 1e-4 per unit of magnitude.  The bf16 matrix-core path rounds the
     pre-scaled Q_aug = [scale_c q || scale_p f_q] * log2(e) to bf16 once (round to nearest: relative
-    error at most 2^-9 per element), so a logit is perturbed by at most
-        eps = 2^-9 * max_ij sum_c |Q_aug[i][c] * K_aug[j][c]|
+    error at most 2^-8 per element: 8 significant bits), so a logit is perturbed by at most
+        eps = 2^-8 * max_ij sum_c |Q_aug[i][c] * K_aug[j][c]|
     (computed below from the inputs; about 0.3 here).  LSE is 1-Lipschitz in the logits under the
     sup norm, hence |LSE err| <= eps + the usual 2e-2.  A probability moves by a factor of at most
     e^(2 eps), so O and the gradients -- sums of products with P -- move by at most about
@@ -141,7 +141,7 @@ def test_large_logits_need_the_row_max(oracle, gh):
                 fb = np.abs(x["f_k"][hd]).astype(np.float64)
                 # content and positional parts pair different token orders; bound each by its own maximum
                 eps = max(eps, float((qa @ ka.T).max() + (fa @ fb.T).max()))
-            eps *= 2.0 ** -9
+            eps *= 2.0 ** -8
             print(f"big-bf16: logit perturbation bound eps = {eps:.3f}", flush=True)
             tol, tol_lse = 0.15, eps + 2e-2
         t = gh.device_inputs(wl, x)
@@ -230,8 +230,8 @@ def _sign_codes(N, r):
 def _logit_eps(wl, x):
     """Largest perturbation of a logit by the ONE rounding the bf16 matrix-core kernels apply to
     their operands: Q_aug = [scale_c q || scale_p f_q] * log2(e) is rounded to bf16 (relative error
-    at most 2^-9 per element; k, f_k enter as given), so
-        |logit err| <= eps = 2^-9 * max over (window, head, i, j) of sum_c |Q_aug[i][c] K_aug[j][c]|.
+    at most 2^-8 per element: 8 significant bits; k, f_k enter as given), so
+        |logit err| <= eps = 2^-8 * max over (window, head, i, j) of sum_c |Q_aug[i][c] K_aug[j][c]|.
     Computed here from the inputs with absolute values (no arithmetic of the method)."""
     from helpers import partition
     qa = np.abs(partition(x["q"].astype(np.float64), wl.M, wl.s))
@@ -242,7 +242,7 @@ def _logit_eps(wl, x):
         pos = wl.scale_p * (np.abs(x["f_q"][hd].astype(np.float64)) @ np.abs(x["f_k"][hd].astype(np.float64)).T)
         for w in range(qa.shape[0]):
             worst = max(worst, float((wl.scale_c * (qa[w][:, ch] @ ka[w][:, ch].T) + pos).max()))
-    return worst * 2.0 ** -9
+    return worst * 2.0 ** -8
 
 
 def _check_all(oracle, gh, wl, x, flags=0):

@@ -135,6 +135,29 @@ rib_status rib_window_attn_bwd(const rib_params *p,
                                float *df_q, float *df_k,
                                void *workspace, size_t workspace_bytes, void *stream);
 
+/* Size of the library's own backward scratch (see below): a static device array of
+ * this many bytes, which every GPU the library is loaded on holds until the process
+ * ends. */
+#define RIB_STATIC_SCRATCH_BYTES (32u << 20)
+
+/* rib_window_attn_bwd for callers that cannot allocate device memory or hand over
+ * a workspace: code under HIP graph capture, tight serving / training loops,
+ * harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and
+ * errors as rib_window_attn_bwd, but the scratch is a static device array inside
+ * the library; the call allocates nothing, frees nothing and calls no allocating
+ * routine.  Problems whose rib_window_attn_bwd_workspace_bytes exceed
+ * RIB_STATIC_SCRATCH_BYTES are rejected with RIB_ERR_WORKSPACE before anything is
+ * launched.  All calls on one GPU share that GPU's array: calls that overlap in
+ * time on the same GPU (different streams or threads) race on it; calls on one
+ * stream, or otherwise ordered, are safe.  Nothing in the array has to start at
+ * zero and nothing is kept in it between calls. */
+rib_status rib_window_attn_bwd_static_scratch(const rib_params *p,
+                                              const void *q, const void *k, const void *v,
+                                              const void *f_q, const void *f_k,
+                                              const void *out, const void *d_out, const float *lse,
+                                              void *dq, void *dk, void *dv,
+                                              float *df_q, float *df_k, void *stream);
+
 /* ------------------------------------------------------------------------
  * Gated variants: the convolutional-local-attention gate of the paper's Sec. 3.2
  * Eq. 9, O' = O (.) G, applied in the attention kernel's epilogue instead of in

@@ -25,7 +25,9 @@ STATUS_NAMES = {0: "RIB_OK", 1: "RIB_ERR_NULL", 2: "RIB_ERR_SHAPE", 3: "RIB_ERR_
 EXPORTS = ("rib_window_attn_fwd", "rib_window_attn_bwd", "rib_window_attn_bwd_workspace_bytes",
            "rib_status_string", "rib_window_attn_kernel_name",
            "rib_features_fwd", "rib_features_bwd", "rib_features_bwd_workspace_bytes",
-           "rib_window_attn_gated_fwd", "rib_window_attn_gated_bwd", "rib_window_attn_gated_bwd_workspace_bytes")
+           "rib_window_attn_gated_fwd", "rib_window_attn_gated_bwd", "rib_window_attn_gated_bwd_workspace_bytes",
+           "rib_window_attn_bwd_static_scratch")
+RIB_STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class RibParams(ctypes.Structure):
@@ -70,6 +72,8 @@ def load() -> ctypes.CDLL:
     lib.rib_window_attn_bwd_workspace_bytes.argtypes = [pp]
     lib.rib_window_attn_bwd.restype = ctypes.c_int
     lib.rib_window_attn_bwd.argtypes = [pp] + [vp] * 13 + [vp, ctypes.c_size_t, vp]
+    lib.rib_window_attn_bwd_static_scratch.restype = ctypes.c_int
+    lib.rib_window_attn_bwd_static_scratch.argtypes = [pp] + [vp] * 13 + [vp]
     lib.rib_status_string.restype = ctypes.c_char_p
     lib.rib_status_string.argtypes = [ctypes.c_int]
     lib.rib_window_attn_kernel_name.restype = ctypes.c_char_p
@@ -164,6 +168,22 @@ def rib_window_attn_bwd(p, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q,
                                     workspace, workspace_bytes, stream)
     if st != RIB_OK:
         raise RibError(st, "rib_window_attn_bwd")
+
+
+def rib_window_attn_bwd_static_scratch_status(p, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k,
+                                              stream=None) -> int:
+    return load().rib_window_attn_bwd_static_scratch(ctypes.byref(p) if p is not None else None, _ptr(q), _ptr(k),
+                                                     _ptr(v), _ptr(f_q), _ptr(f_k), _ptr(out), _ptr(d_out),
+                                                     _ptr(lse), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(df_q), _ptr(df_k),
+                                                     _stream(stream) if stream != 0 else 0)
+
+
+def rib_window_attn_bwd_static_scratch(p, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k,
+                                       stream=None) -> None:
+    st = rib_window_attn_bwd_static_scratch_status(p, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k,
+                                                   stream)
+    if st != RIB_OK:
+        raise RibError(st, "rib_window_attn_bwd_static_scratch")
 
 
 def rib_window_attn_gated_fwd_status(p, q, k, v, f_q, f_k, gate, out_gated, out_raw, lse, stream=None) -> int:

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/rib_attn.h: argument validation,
 // kernel-family selection and launches.  Nothing here allocates device memory or
 // synchronises.
+#include <atomic>
 #include <cmath>
 #include <mutex>
 #include <set>
@@ -8,10 +9,39 @@
 
 #include "rib_common.h"
 
+// Scratch of rib_window_attn_bwd_static_scratch: device memory that exists from the moment the
+// code object is loaded, so that the entry point has nothing to allocate.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; every GPU holds its own copy at its own
+// address, looked up once per device and cached below.  (The host-side reference in
+// static_scratch() is what makes the compiler export the symbol from the code object; no
+// attribute may be added here: `used` turns it into a local symbol the runtime cannot find.)
+static __device__ __align__(256) unsigned char scratch[RIB_STATIC_SCRATCH_BYTES];
+
 namespace rib {
 namespace {
 
 constexpr int kMaxDevices = 64;
+std::atomic<void *> scratch_ptr[kMaxDevices];
+
+// Address of the current device's copy of `scratch` (nullptr and *err set on failure).
+void *static_scratch(hipError_t *err)
+{
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= kMaxDevices) {
+        *err = hipErrorInvalidDevice;
+        return nullptr;
+    }
+    void *ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        *err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess) return nullptr;
+        scratch_ptr[dev].store(ptr, std::memory_order_release);      // (racing threads store the same address)
+    }
+    return ptr;
+}
+
 // Validate everything that does not involve data pointers and fill Geo.
 rib_status make_geo(const rib_params *p, Geo *g)
 {
@@ -232,6 +262,24 @@ rib_status rib_window_attn_bwd(const rib_params *p, const void *q, const void *k
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < valu_bwd_workspace(g))
         return RIB_ERR_WORKSPACE;
     return enqueue_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, workspace,
+                       (hipStream_t)stream);
+}
+
+rib_status rib_window_attn_bwd_static_scratch(const rib_params *p, const void *q, const void *k, const void *v,
+                                              const void *f_q, const void *f_k, const void *out, const void *d_out,
+                                              const float *lse, void *dq, void *dk, void *dv, float *df_q,
+                                              float *df_k, void *stream)
+{
+    Geo g;
+    rib_status st = check_bwd(p, &g, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k);
+    if (st != RIB_OK) return st;
+    if (valu_bwd_workspace(g) > (size_t)RIB_STATIC_SCRATCH_BYTES) return RIB_ERR_WORKSPACE;
+    hipError_t e;
+    void *ws = static_scratch(&e);
+    if (ws == nullptr) return RIB_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: the delta pass and the main kernels write every
+    // element the later kernels of the same call read.
+    return enqueue_bwd(g, p->dtype, q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k, ws,
                        (hipStream_t)stream);
 }
 

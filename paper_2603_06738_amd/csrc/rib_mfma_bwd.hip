@@ -511,7 +511,13 @@ struct LayT {
     static constexpr int KS = DQK / 16, VS = DVK / 16;
 };
 
-constexpr float kTruncGain = 1.0028176f;   // 1 + 2^-8 / (2 ln 2): mean relative loss of bf16 truncation
+// P and dS go to bf16 by truncation, which loses half a unit in the last place on average
+// (relative 2^-8 * 0.7213 for log-uniform mantissas).  The loss is made up BEFORE the truncation:
+// this constant is added to the -LSE * log2(e) that rides with every logit, so P (and with it
+// dS = P (dP - delta)) is scaled up by the mean loss and then truncated.  Values that are exactly
+// representable (P = 1 of a one-hot row, P = 2^-k of a uniform row) come through unchanged, the
+// others are right on average.
+constexpr float kTruncLog2 = 0.0040593f;   // log2(1 + 2^-8 * 0.7213)
 
 __device__ __forceinline__ uint32_t trunc_pack(float lo, float hi)
 {
@@ -643,13 +649,13 @@ __device__ __forceinline__ void fstore(const FRegs<DQK, DVK> &rg, const FConst<D
     if (XC) {
         if (QDO && threadIdx.x < kT) {
             float *ex = (float *)(S + L::EX);
-            ex[threadIdx.x] = -rg.e0 * kLog2e;
+            ex[threadIdx.x] = kTruncLog2 - rg.e0 * kLog2e;
             ex[kT + threadIdx.x] = -rg.e1;
         }
     } else if (threadIdx.x < kT) {
         uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
         if (QDO) {
-            ex = split_bf16(-rg.e0 * kLog2e);
+            ex = split_bf16(kTruncLog2 - rg.e0 * kLog2e);
             ey = split_bf16(-rg.e1);
         }
         *(uint32_t *)(S + L::XR + threadIdx.x * L::XS + DQK - 2) = ex;
@@ -715,7 +721,7 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
     if (!XC) {
         uint32_t ex = 0x3f803f80u, ey = 0x3f803f80u;
         if (QDO) {
-            ex = split_bf16(-e0 * kLog2e);
+            ex = split_bf16(kTruncLog2 - e0 * kLog2e);
             ey = split_bf16(-e1);
         }
         *(uint32_t *)(Xs + lane * L::XS + DQK - 2) = ex;
@@ -866,7 +872,7 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
     if (XC) {
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            nl[qb] = -lse[u * g.N + q0 + qb * 32 + col] * kLog2e;
+            nl[qb] = kTruncLog2 - lse[u * g.N + q0 + qb * 32 + col] * kLog2e;
             nd[qb] = -delta[u * g.N + q0 + qb * 32 + col];
         }
     }
@@ -921,8 +927,8 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) stash_block(acc[qb][mb], mb, hf, As + (qb * 32 + col) * kARS);
     __builtin_amdgcn_wave_barrier();
-    flush_rows(As, g.scale_c * kTruncGain, dq, tok, q0, hd, g);
-    flush_partial(As, g.scale_p * kTruncGain, dfq_part + (u * g.N + q0) * g.r, g);
+    flush_rows(As, g.scale_c, dq, tok, q0, hd, g);
+    flush_partial(As, g.scale_p, dfq_part + (u * g.N + q0) * g.r, g);
 }
 
 // dK, dV (+ dF_k partial), fast path.
@@ -957,10 +963,14 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
 
     const int k0 = (blk * kWaves + wave) * 64;
     bf16x8 Kb[2][L::KS], Vb[2][L::VS];
-    stationary_rows<DQK, DVK, false, true, XC>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, sc2, sp2,
-                                     smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
+    // The logits must be the forward's bit for bit, or P = exp2(S - LSE) is off by the difference of
+    // two roundings (for logits of size 100 that is a factor, not a rounding error): Q_aug is scaled
+    // and rounded exactly as the forward and the dq kernel do it -- here on the streamed side, a few
+    // vector instructions per tile -- and K_aug enters as it is.
+    stationary_rows<DQK, DVK, false, false, XC>(g, hd, u, k0, tok, (const char *)k, (const char *)v, fk, lse, delta, 1.f, 1.f,
+                                      smem + wave * (64 * L::XS + 64 * L::YS), Kb, Vb);
     clear_stage_pads<DQK, DVK, T, kNT, XC>(g, stage0, stage1);
-    fstore<DQK, DVK, T, true, true, false, XC>(rg, c, stage0, sc2, sp2);
+    fstore<DQK, DVK, T, true, true, true, XC>(rg, c, stage0, sc2, sp2);
     fload<DQK, DVK, T, true>(rg, c, g, u, ntiles > 1 ? 1 : 0, tok, qb_, gb_, fqb, lse, delta);
     __syncthreads();
 
@@ -1046,7 +1056,7 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
         }
         {
             const FConst<DQK, DVK, T> cc = fconst<DQK, DVK, T>(g, hd, opaque_tid());
-            fstore<DQK, DVK, T, true, true, false, XC>(rg, cc, nxt, sc2, sp2);
+            fstore<DQK, DVK, T, true, true, true, XC>(rg, cc, nxt, sc2, sp2);
             fload<DQK, DVK, T, true>(rg, cc, g, u, tile + 2 < ntiles ? tile + 2 : ntiles - 1, tok, qb_, gb_, fqb, lse,
                                      delta);
         }
@@ -1060,13 +1070,14 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) stash_block(accK[kb][mb], mb, hf, As + (kb * 32 + col) * kARS);
     __builtin_amdgcn_wave_barrier();
-    flush_rows(As, g.scale_c * kTruncGain, dk, tok, k0, hd, g);
-    flush_partial(As, g.scale_p * kTruncGain, dfk_part + (u * g.N + k0) * g.r, g);
+    // (the streamed Q_aug rows carry scale * log2 e: undo the log2 e here)
+    flush_rows(As, kLn2, dk, tok, k0, hd, g);
+    flush_partial(As, kLn2, dfk_part + (u * g.N + k0) * g.r, g);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) stash_block(accV[kb], 0, hf, As + (kb * 32 + col) * kARS);
     __builtin_amdgcn_wave_barrier();
-    flush_rows(As, kTruncGain, dv, tok, k0, hd, g);
+    flush_rows(As, 1.f, dv, tok, k0, hd, g);
 }
 
 static bool bwd_fast_ok(const Geo &g)

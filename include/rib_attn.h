@@ -36,7 +36,9 @@
  *
  * Conventions for every entry point
  *   - Every data pointer is a DEVICE pointer owned by the caller, valid on the
- *     current HIP device.  Unless an entry point says otherwise the library
+ *     current HIP device, and at least 4-byte aligned (the kernels move bf16
+ *     values in pairs; 16-byte alignment, as allocators give, is the fast case).
+ *     A misaligned pointer is rejected with RIB_ERR_SHAPE.  Unless an entry point says otherwise the library
  *     allocates nothing, frees nothing and keeps no pointer after returning.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Work
  *     is enqueued asynchronously; nothing synchronises.
@@ -44,7 +46,10 @@
  *     validation returns an error code and touches no memory.  No C++ exception
  *     crosses the boundary.
  *   - Outputs must not overlap inputs or each other.
- *   - Entry points are thread-safe (no mutable global state).
+ *   - Entry points are thread-safe.  The only state the library keeps is a record, per
+ *     device, of one-time set-up (a kernel's dynamic-LDS limit raised, the number
+ *     of compute units, the address of the static scratch below); a failed
+ *     set-up is not remembered and is tried again by the next call.
  */
 #ifndef RIB_ATTN_H
 #define RIB_ATTN_H
@@ -59,7 +64,8 @@ extern "C" {
 typedef enum {
     RIB_OK = 0,
     RIB_ERR_NULL = 1,        /* a required pointer is NULL */
-    RIB_ERR_SHAPE = 2,       /* non-positive size, H or W not a multiple of window, shift out of range, bad stride */
+    RIB_ERR_SHAPE = 2,       /* non-positive size, H or W not a multiple of window, shift out of range, bad stride,
+                                unknown flag bit, data pointer not 4-byte aligned */
     RIB_ERR_DTYPE = 3,       /* dtype is not one of rib_dtype */
     RIB_ERR_UNSUPPORTED = 4, /* valid problem, but d / r beyond what the kernels are built for */
     RIB_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than rib_window_attn_bwd_workspace_bytes */

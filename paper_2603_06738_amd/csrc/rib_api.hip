@@ -3,6 +3,7 @@
 // synchronises.
 #include <atomic>
 #include <cmath>
+#include <initializer_list>
 #include <mutex>
 #include <set>
 #include <utility>
@@ -54,6 +55,7 @@ rib_status make_geo(const rib_params *p, Geo *g)
     if (p->token_stride != 0 && p->token_stride < C) return RIB_ERR_SHAPE;
     if (!std::isfinite(p->scale_c) || !std::isfinite(p->scale_p)) return RIB_ERR_SHAPE;
     if (p->dtype != RIB_F32 && p->dtype != RIB_BF16) return RIB_ERR_DTYPE;
+    if ((p->flags & ~(RIB_FLAG_FORCE_ROW_MAX | RIB_FLAG_WIDE | RIB_FLAG_VECTOR_ONLY)) != 0) return RIB_ERR_SHAPE;
     if (p->d > 64 || p->r > 64 || (int64_t)p->window * p->window > 65536 || C > (1 << 20))
         return RIB_ERR_UNSUPPORTED;
     g->B = p->B; g->H = p->H; g->W = p->W;
@@ -77,6 +79,15 @@ rib_status make_geo(const rib_params *p, Geo *g)
     return RIB_OK;
 }
 
+// The kernels read and write the tensors in 4-byte pieces (bf16 pairs, fp32 values): every
+// data pointer must be 4-byte aligned (NULL passes; presence is checked separately).
+bool aligned4(std::initializer_list<const void *> ptrs)
+{
+    for (const void *ptr : ptrs)
+        if (((uintptr_t)ptr & 3) != 0) return false;
+    return true;
+}
+
 rib_status check_bwd(const rib_params *p, Geo *g, const void *q, const void *k, const void *v, const void *f_q,
                      const void *f_k, const void *out, const void *d_out, const float *lse, void *dq, void *dk,
                      void *dv, float *df_q, float *df_k)
@@ -85,6 +96,7 @@ rib_status check_bwd(const rib_params *p, Geo *g, const void *q, const void *k, 
     if (st != RIB_OK) return st;
     if (!q || !k || !v || !out || !d_out || !lse || !dq || !dk || !dv) return RIB_ERR_NULL;
     if (g->r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
+    if (!aligned4({q, k, v, f_q, f_k, out, d_out, lse, dq, dk, dv, df_q, df_k})) return RIB_ERR_SHAPE;
     return RIB_OK;
 }
 
@@ -174,6 +186,7 @@ rib_status rib_window_attn_fwd(const rib_params *p, const void *q, const void *k
     if (st != RIB_OK) return st;
     if (!q || !k || !v || !out) return RIB_ERR_NULL;
     if (g.r > 0 && (!f_q || !f_k)) return RIB_ERR_NULL;
+    if (!aligned4({q, k, v, f_q, f_k, out, lse})) return RIB_ERR_SHAPE;
     hipError_t e;
     if (mfma_fwd_supported(g, p->dtype))
         e = launch_mfma_fwd(g, (p->flags & RIB_FLAG_FORCE_ROW_MAX) != 0, q, k, v, f_q, f_k, out, lse,
@@ -194,6 +207,7 @@ rib_status rib_window_attn_gated_fwd(const rib_params *p, const void *q, const v
     if (st != RIB_OK) return st;
     if (!q || !k || !v || !gate || !out_gated) return RIB_ERR_NULL;
     if (g.r > 0 && (!f_q || !f_k)) return RIB_ERR_NULL;
+    if (!aligned4({q, k, v, f_q, f_k, gate, out_gated, out_raw, lse})) return RIB_ERR_SHAPE;
     g.gate = gate;
     g.out_raw = out_raw;
     hipError_t e;
@@ -224,6 +238,7 @@ rib_status rib_window_attn_gated_bwd(const rib_params *p, const void *q, const v
     if (st != RIB_OK) return st;
     if (!q || !k || !v || !gate || !out_raw || !d_out_gated || !lse || !dq || !dk || !dv || !dgate) return RIB_ERR_NULL;
     if (g.r > 0 && (!f_q || !f_k || !df_q || !df_k)) return RIB_ERR_NULL;
+    if (!aligned4({q, k, v, f_q, f_k, gate, out_raw, d_out_gated, lse, dq, dk, dv, dgate, df_q, df_k})) return RIB_ERR_SHAPE;
     const size_t base = valu_bwd_workspace(g);
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < base + gated_dout_bytes(g, p->dtype))
         return RIB_ERR_WORKSPACE;

@@ -65,18 +65,19 @@ def unpartition(a, B, H, W, M, s):
     return np.roll(a, (s, s), axis=(1, 2))
 
 
-def concat_form_fwd(wl, x):
+def concat_form_fwd(wl, x, dtype=np.float64):
     """Eq. 5: Q = [scale_c*q || scale_p*f_q], K = [k || f_k], one dot product,
-    softmax, PV -- in numpy float64 over explicitly partitioned windows."""
-    qs, ks, vs = (partition(x[n].astype(np.float64), wl.M, wl.s) for n in ("q", "k", "v"))
+    softmax, PV -- in numpy over explicitly partitioned windows, every operation in
+    `dtype` (float64 unless a test asks for single precision)."""
+    qs, ks, vs = (partition(x[n].astype(dtype), wl.M, wl.s) for n in ("q", "k", "v"))
     nW, N, d = qs.shape[0], wl.N, wl.d
     O = np.zeros_like(qs)
-    lse = np.zeros((nW, wl.heads, N))
+    lse = np.zeros((nW, wl.heads, N), dtype)
     for hd in range(wl.heads):
         ch = slice(hd * d, (hd + 1) * d)
-        fq = np.broadcast_to(x["f_q"][hd].astype(np.float64), (nW, N, wl.r))
-        fk = np.broadcast_to(x["f_k"][hd].astype(np.float64), (nW, N, wl.r))
-        Q = np.concatenate([wl.scale_c * qs[..., ch], wl.scale_p * fq], axis=-1)
+        fq = np.broadcast_to(x["f_q"][hd].astype(dtype), (nW, N, wl.r))
+        fk = np.broadcast_to(x["f_k"][hd].astype(dtype), (nW, N, wl.r))
+        Q = np.concatenate([dtype(wl.scale_c) * qs[..., ch], dtype(wl.scale_p) * fq], axis=-1)
         K = np.concatenate([ks[..., ch], fk], axis=-1)
         S = Q @ K.transpose(0, 2, 1)
         mx = S.max(-1, keepdims=True)

@@ -63,6 +63,20 @@ def test_dtype_and_unsupported_errors():
     assert fwd_status(good(H=512, W=512, window=512)) == 4
 
 
+def test_unknown_flags_and_misaligned_pointers_are_rejected():
+    assert fwd_status(good(flags=8)) == 2
+    assert fwd_status(good(flags=1 << 20)) == 2
+    for name in ("q", "k", "v", "f_q", "f_k", "out"):
+        assert fwd_status(good(), **{name: FAKE + 2}) == 2
+        assert fwd_status(good(dtype="bf16"), **{name: FAKE + 1}) == 2
+    p = good()
+    args = [FAKE] * 13
+    for i in range(13):
+        bad = list(args)
+        bad[i] = FAKE + 2
+        assert rb.rib_window_attn_bwd_status(p, *bad, FAKE, 1 << 30, stream=0) == 2
+
+
 def test_null_pointer_errors():
     assert rb.rib_window_attn_fwd_status(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None, stream=0) == 1
     for name in ("q", "k", "v", "out", "f_q", "f_k"):

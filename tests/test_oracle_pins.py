@@ -300,6 +300,20 @@ def test_bf16_input_rounding_is_shared_not_hidden(oracle):
     np.testing.assert_array_equal(torch.tensor(raw["q"]).bfloat16().float().numpy(), x["q"])
 
 
+def test_single_precision_evaluation_agrees_on_bf16_inputs(oracle):
+    """The oracle in double against the plain definition (Eq. 5 concat form over explicit
+    windows) evaluated entirely in float32, on bf16-rounded inputs of the paper's head shape:
+    they agree to 1e-4, i.e. the arithmetic precision of the reference is not what the bf16
+    tolerance of 2e-2 has to absorb -- the GPU's own bf16 operands are."""
+    wl = wk.custom("p9", "bf16", 2, 32, 16, 2, 30, 16, 16, 5, 132)
+    x = wk.make_inputs(wl)
+    O, lse = oracle.fwd(geometry(oracle, wl), x["q"], x["k"], x["v"], x["f_q"], x["f_k"])
+    O32, lse32 = concat_form_fwd(wl, x, dtype=np.float32)
+    assert O32.dtype == np.float32 and lse32.dtype == np.float32
+    assert np.abs(O - O32).max() <= 1e-4
+    assert np.abs(lse - lse32).max() <= 1e-4
+
+
 def test_gate_of_ones_is_the_plain_operator(oracle):
     wl = wk.custom("gate1", "f32", 1, 4, 8, 2, 3, 2, 4, 1, 121, backward=True)
     x = wk.make_inputs(wl)

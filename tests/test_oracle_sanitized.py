@@ -14,7 +14,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
     exe = str(tmp_path / "oracle_sanitized")
     cmd = ["gcc", "-O1", "-g", "-std=c99", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
-           "-static-libasan", "-o", exe,     # (runtime linked in: no ordering demands on preloaded libraries) os.path.join(ROOT, "oracle", "rib_oracle.c"),
+           "-static-libasan",       # runtime linked in: no ordering demands on preloaded libraries
+           "-o", exe, os.path.join(ROOT, "oracle", "rib_oracle.c"),
            os.path.join(ROOT, "oracle", "sanitize_check.c"), "-lm"]
     built = subprocess.run(cmd, capture_output=True, text=True)
     if built.returncode != 0 and "asan" in built.stderr.lower():

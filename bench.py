@@ -16,6 +16,7 @@ the timed region starts.  Prints ONE JSON line.
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -26,11 +27,13 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, vendor figure
 PEAK_F32_VALU_TFLOPS = 157.3  # MI355X fp32 vector, vendor figure
 PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 MFMA, vendor figure
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a
-# plain copy of known size (profiles/c5_step_hbm_traffic.md); only for the workload it was measured on.
-MEASURED_FWD_TRAFFIC = {"c5": 230.6e6}
-# the same for the backward's launches (delta 109.7 + dkv 449.5 + dq 370.2 + reduce 114.1 MB)
-MEASURED_BWD_TRAFFIC = {"c5": 1043.5e6}
+# HBM bytes per launch are NOT measured by this script (that takes rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by a plain copy of known size).  Where such a run of this very workload is committed under profiles/,
+# its figure is quoted in `traffic_from_profile` with the file it comes from; `traffic` itself stays null.
+PROFILED_TRAFFIC = {
+    "c5": {"forward": {"bytes": 230.6e6, "source": "profiles/c5_step_hbm_traffic.md"},
+           "backward": {"bytes": 1043.5e6, "source": "profiles/c5_step_hbm_traffic.md"}},
+}
 
 
 def parse():
@@ -42,8 +45,14 @@ def parse():
     ap.add_argument("--dtype", choices=["bf16", "f32"], default=None,
                     help="run the workload in this storage type instead of its own (fp32: the fp32 MFMA kernels)")
     ap.add_argument("--all", action="store_true", help="also time the forward of every named workload")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="cycle the steps through this many distinct sets of buffers, so that a workload smaller than "
+                         "the 256 MB Infinity Cache is read from HBM (for counter runs on the small-window configs)")
     ap.add_argument("--force-row-max", action="store_true", help="time the max-tracking softmax path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-c3", action="store_true", help="skip the extra forward run of config 3")
+    ap.add_argument("--no-kernel-table", action="store_true",
+                    help="skip the torch.profiler pass (use under rocprofv3: two tracers in one process disagree)")
     ap.add_argument("--cpu-units", type=int, default=0, help="units in the CPU-oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -90,22 +99,25 @@ class Runner:
                                     self.lse, self.dq, self.dk, self.dv, self.dfq, self.dfk, self.ws)
 
 
-def time_steps(r, steps, warmup):
-    """Returns (wall ms per step, mean fwd ms, mean bwd ms) with HIP events on the launch stream."""
+def time_steps(r, steps, warmup, others=()):
+    """Returns (wall ms per step, mean fwd ms, mean bwd ms) with HIP events on the launch stream.
+    `others`: further Runners of the same workload; the steps then cycle through all of them."""
     torch = r.torch
-    for _ in range(warmup):
-        r.fwd()
+    ring = (r,) + tuple(others)
+    for i in range(warmup):
+        ring[i % len(ring)].fwd()
         if r.wl.backward:
-            r.bwd()
+            ring[i % len(ring)].bwd()
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
     t0 = time.perf_counter()
     for s in range(steps):
+        cur = ring[s % len(ring)]
         ev[s][0].record()
-        r.fwd()
+        cur.fwd()
         ev[s][1].record()
         if r.wl.backward:
-            r.bwd()
+            cur.bwd()
         ev[s][2].record()
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) * 1e3 / steps
@@ -114,6 +126,45 @@ def time_steps(r, steps, warmup):
     r.last_stats = {"fwd_ms_median": round(f[len(f) // 2], 4), "fwd_ms_min": round(f[0], 4),
                     "bwd_ms_median": round(b[len(b) // 2], 4), "bwd_ms_min": round(b[0], 4)}
     return wall, sum(f) / steps, sum(b) / steps
+
+
+def kernel_flop(name, wl):
+    """(algorithmic flop per launch, note) of one of the library's kernels, by name.  The backward's
+    5 contractions (2 N^2 (5d + 3r) per unit) are split without double counting: the dkv kernel gets the
+    scores, dP, dV and dK_aug (4d + 2r), the dq kernel only dQ_aug (d + r): the scores and dP it
+    recomputes are overhead of the two-kernel split, not algorithmic work."""
+    per = 2.0 * wl.N * wl.N * wl.n_units
+    if "fwd" in name:
+        return wl.fwd_flop, "S, PV"
+    if "dkv" in name:
+        return per * (4 * wl.d + 2 * wl.r), "S, dP, dV, dK_aug"
+    if "dq" in name:
+        return per * (wl.d + wl.r), "dQ_aug (S and dP are recomputed: not counted)"
+    return 0.0, "memory-bound helper"
+
+
+def profile_kernels(r, steps=20):
+    """Average device time per launch of every kernel of one step, from a torch.profiler (roctracer) pass over
+    `steps` steps.  The pass is separate from the timed region (tracing slows the launches a little)."""
+    try:
+        from torch.profiler import profile, ProfilerActivity
+        torch = r.torch
+        with profile(activities=[ProfilerActivity.CUDA]) as prof:
+            for _ in range(steps):
+                r.fwd()
+                if r.wl.backward:
+                    r.bwd()
+            torch.cuda.synchronize()
+        out = {}
+        for e in prof.key_averages():
+            if "rib::" not in e.key or e.count == 0:
+                continue
+            m = re.search(r"(\w+_kernel)(<[^(]*>)?", e.key)
+            short = (m.group(1) + (m.group(2) or "")) if m else e.key[:60]
+            out[short] = {"avg_us": round(e.device_time_total / e.count, 2), "calls": int(e.count)}
+        return out
+    except Exception as exc:       # no tracer in this build of torch: the aggregate figures still stand
+        return {"error": repr(exc)}
 
 
 def time_cold(wl, flags, sets=4, reps=40):
@@ -234,7 +285,9 @@ def main():
     flags = rb.RIB_FLAG_FORCE_ROW_MAX if a.force_row_max else 0
 
     r = Runner(wl, flags)
-    wall, fwd_ms, bwd_ms = time_steps(r, a.steps, a.warmup)
+    others = [Runner(wl, flags) for _ in range(max(1, a.rotate) - 1)]
+    wall, fwd_ms, bwd_ms = time_steps(r, a.steps, a.warmup, others)
+    del others
     step_flop = wl.fwd_flop + (wl.bwd_flop if wl.backward else 0.0)
     value = step_flop / (wall * 1e-3) / 1e12
 
@@ -247,7 +300,7 @@ def main():
         "config": {"workload": f"{wl.name}: {'fwd+bwd' if wl.backward else 'fwd'} {wl.dtype} "
                                f"B={wl.B} H=W={wl.H} C={wl.C} heads={wl.heads} d={wl.d} r={wl.r} "
                                f"window={wl.M} shift={wl.s}",
-                   "softmax_path": "row-max" if a.force_row_max else "auto",
+                   "softmax_path": "row-max" if a.force_row_max else "auto", "buffer_sets": max(1, a.rotate),
                    "kernels": {"fwd": rb.kernel_name(r.p, False), "bwd": rb.kernel_name(r.p, True)}},
         "tokens_per_s": round(wl.tokens / (wall * 1e-3), 1),
         "fwd_ms": round(fwd_ms, 4), "fwd_tflops": round(fwd_tflops, 2),
@@ -259,22 +312,55 @@ def main():
         res.update(bwd_ms=round(bwd_ms, 4), bwd_tflops=round(bwd_tflops, 2),
                    bwd_pct_bf16_peak=round(100 * bwd_tflops / PEAK_BF16_TFLOPS, 2),
                    bwd_ms_median=r.last_stats["bwd_ms_median"], bwd_ms_min=r.last_stats["bwd_ms_min"])
-    # roofline of the forward kernel (one launch per step; algorithmic flop of the unpadded dims)
+    # Rooflines.  fwd / bwd: HIP events of this run around the library calls (the forward is ONE kernel launch,
+    # the backward four).  `roofline` is the kernel that takes the largest share of the step, timed per launch by
+    # a torch.profiler pass of this same process (events cannot separate launches made inside one library call).
     fam = rb.kernel_name(r.p, False)
-    mfma = fam == "mfma-bf16"
     peak, bound = family_peak(fam)
-    res["roofline"] = {"kernel": "forward (" + fam + ")",
-                       "bound": bound, "achieved": round(fwd_tflops, 2), "peak": peak,
-                       "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4),
-                       "traffic": MEASURED_FWD_TRAFFIC.get(wl.name),
-                       "algorithmic_flop": wl.fwd_flop, "algorithmic_bytes": wl.fwd_bytes,
-                       "issue_ceiling_tflops": 1318.0 if mfma and wl.d == 30 and wl.r == 16 else None}
+    prof_traffic = PROFILED_TRAFFIC.get(wl.name, {})
+    res["roofline_fwd"] = {"kernel": "forward (" + fam + "), one launch", "bound": bound, "achieved": round(fwd_tflops, 2),
+                           "peak": peak, "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4), "traffic": None,
+                           "traffic_from_profile": prof_traffic.get("forward"),
+                           "algorithmic_flop": wl.fwd_flop, "algorithmic_bytes": wl.fwd_bytes,
+                           "time_source": "HIP events on the launch stream, this run"}
     if wl.backward:
         bpeak, bbound = family_peak(rb.kernel_name(r.p, True))
-        res["roofline_bwd"] = {"kernel": "backward (" + rb.kernel_name(r.p, True) + ", all its launches)",
+        res["roofline_bwd"] = {"kernel": "backward (" + rb.kernel_name(r.p, True) + "), all its launches",
                                "bound": bbound, "achieved": round(bwd_tflops, 2),
-                               "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4),
-                               "traffic": MEASURED_BWD_TRAFFIC.get(wl.name), "algorithmic_flop": wl.bwd_flop}
+                               "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4), "traffic": None,
+                               "traffic_from_profile": prof_traffic.get("backward"),
+                               "algorithmic_flop": wl.bwd_flop, "time_source": "HIP events on the launch stream, this run"}
+    kern = {} if a.no_kernel_table else profile_kernels(r)
+    res["kernels"] = kern
+    dominant = None
+    for name, k in kern.items():
+        if not isinstance(k, dict) or "avg_us" not in k:
+            continue
+        flop, what = kernel_flop(name, wl)
+        fam_k = rb.kernel_name(r.p, "fwd" not in name)
+        pk, bd = family_peak(fam_k)
+        k.update(algorithmic_flop=flop, counts=what)
+        if flop > 0:
+            tf = flop / (k["avg_us"] * 1e-6) / 1e12
+            k.update(tflops=round(tf, 1), frac=round(tf / pk, 4), peak=pk, bound=bd)
+        if dominant is None or k["avg_us"] * k["calls"] > kern[dominant]["avg_us"] * kern[dominant]["calls"]:
+            dominant = name
+    if dominant is not None and "frac" in kern[dominant]:
+        k = kern[dominant]
+        res["roofline"] = {"kernel": dominant, "bound": k["bound"], "achieved": k["tflops"], "peak": k["peak"],
+                           "unit": "TFLOP/s", "frac": k["frac"], "traffic": None, "algorithmic_flop": k["algorithmic_flop"],
+                           "avg_launch_us": k["avg_us"],
+                           "time_source": "torch.profiler pass of 20 steps in this run (per-launch device time)"}
+    else:       # no per-kernel times: fall back to the phase that dominates the step
+        res["roofline"] = dict(res["roofline_bwd"] if wl.backward and bwd_ms > fwd_ms else res["roofline_fwd"])
+    # the headline shape of the forward target (config 3, 32x32 windows): a short run of its own
+    if wl.name == "c5" and not a.no_c3:
+        w3 = wk.WORKLOADS["c3"]
+        r3 = Runner(w3, flags)
+        _, f3, _ = time_steps(r3, min(100, max(20, a.steps)), min(a.warmup, 30))
+        tf3 = w3.fwd_flop / (f3 * 1e-3) / 1e12
+        res.update(fwd_c3_ms=round(f3, 4), fwd_c3_tflops=round(tf3, 2), fwd_c3_frac=round(tf3 / PEAK_BF16_TFLOPS, 4))
+        del r3
     del r
     torch.cuda.empty_cache()
 

@@ -1195,6 +1195,9 @@ static int fast_waves(const Geo &g)
           tokens * g.tstride * 2 < ((int64_t)1 << 32) && small_r))
         return 0;
     if (g.N % 512 != 0) return 4;
+#ifdef RIB_TRACE
+    if (getenv("RIB_FORCE_WAVES")) return atoi(getenv("RIB_FORCE_WAVES"));
+#endif
     if (g.flags & RIB_FLAG_WIDE) return 8;
     const bool ones = g.d < 32, narrow = g.d + g.r <= 48;
     return ones && (narrow || g.N >= 4096) ? 8 : 4;

@@ -31,7 +31,6 @@
 //   maximum that is raised lazily (only when a tile exceeds it by 2^8) and is
 //   subtracted for free as the C operand of the score MFMA.  Both paths compute
 //   the exact softmax up to rounding.
-#include <cstdlib>
 
 #include "rib_common.h"
 
@@ -292,27 +291,6 @@ struct FastTile {
     static constexpr int FT = 32 * WAVES;       // keys per tile
     static constexpr int FVS = FT + 8;          // bf16 per V^T row (272 / 528 B: conflict-free 16-byte reads)
 };
-// scheduling-group masks of __builtin_amdgcn_sched_group_barrier
-#define RIB_SG_VALU 0x002
-#define RIB_SG_MFMA 0x008
-#define RIB_SG_VMEM_RD 0x020
-#define RIB_SG_DS_RD 0x100
-#define RIB_SG_DS_WR 0x200
-#define RIB_SG_TRANS 0x400
-#define RIB_SG(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-
-// Emits, for m = M0 .. M1-1: one MFMA, then 3 or 4 transcendentals (16 per 5 MFMAs),
-// then 2 vector-ALU instructions.
-template <int M0, int M1>
-__device__ __forceinline__ void sched_pipeline()
-{
-    if constexpr (M0 < M1) {
-        RIB_SG(RIB_SG_MFMA, 1);
-        RIB_SG(RIB_SG_TRANS, (M0 % 5) == 4 ? 4 : 3);
-        RIB_SG(RIB_SG_VALU, 2);
-        sched_pipeline<M0 + 1, M1>();
-    }
-}
 
 // Two dwords at a 4-byte aligned address (global memory only needs dword alignment for
 // multi-dword accesses; LDS gets them as a two-dword write).
@@ -809,22 +787,6 @@ __device__ __forceinline__ TokMap map_at(const Geo &g, const int *slot)
     return m;
 }
 
-#ifdef RIB_TRACE     // development aid: wall-clock stamps (10 ns units) of wave 0, per workgroup and item
-__device__ unsigned long long rib_trace_buf[1024 * 128];
-#define RIB_STAMP(t, k)                                                                                        \
-    do {                                                                                                       \
-        if (threadIdx.x == 0 && blockIdx.x < 1024 && (t) < 8 && (k) < 16)                                        \
-            rib_trace_buf[blockIdx.x * 128 + (t) * 16 + (k)] = wall_clock64();                                   \
-    } while (0)
-#define RIB_STAMP_CLK(t, k)                                                                                    \
-    do {                                                                                                       \
-        if (threadIdx.x == 0 && blockIdx.x < 1024 && (t) < 8 && (k) < 16)                                        \
-            rib_trace_buf[blockIdx.x * 128 + (t) * 16 + (k)] = clock64();                                        \
-    } while (0)
-#else
-#define RIB_STAMP(t, k) do { } while (0)
-#define RIB_STAMP_CLK(t, k) do { } while (0)
-#endif
 
 
 // Raw q / f_q words of a wave's 64 query rows: 16 lanes per token, 4 tokens per pass.
@@ -979,8 +941,6 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
 #pragma unroll
             for (int i = 0; i < 16; ++i) O[qb][i] = 0.f;
 
-        RIB_STAMP(t, 0);
-        RIB_STAMP_CLK(t, 14);
         for (int tile = 0; tile < ntiles; ++tile) {
             // the map of the item after next goes into the slot the previous item has left; the
             // barrier inside the last tile publishes it
@@ -989,7 +949,6 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
             fast_tile<DQK, ONES, WAVES>(g, lc, kbase, vbase, rg, A, Kf + cur * KSZ, Vf + cur * VSZ, Kf + (cur ^ 1) * KSZ,
                                         Vf + (cur ^ 1) * VSZ, Q, O, lsum);
             advance();
-            RIB_STAMP(t, 5 + tile);
             cur ^= 1;
         }
         // A wave whose rows left the safe range notes the item for the cold path and skips its
@@ -1003,8 +962,6 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
         const bool redo = __any(bad);
         if (redo) redo_flag[t] = 1;
 
-        RIB_STAMP(t, 1);
-        RIB_STAMP_CLK(t, 15);
         const int q0 = ci.blk * NT + wave * 64;
         const TokMap ctok = map_at(g, maps + (t % 3) * map_words);
 
@@ -1015,7 +972,6 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
             q_request<DQK>(qr, g, map_at(g, maps + ((t + 1) % 3) * map_words), ni.hd, ni.blk * NT + wave * 64, tsb, q, fq);
         }
 
-        RIB_STAMP(t, 2);
         if (!redo) {
             // Normalise, then send O through LDS so that the global stores are token rows: in the
             // accumulator layout a lane holds 16 channels of ONE token, and storing from there would
@@ -1062,12 +1018,10 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
             }
         }
 
-        RIB_STAMP(t, 3);
         if (t + 1 < my_n) {
             ci = ni;
             q_stage<DQK>(qr, g, Ws, padw, Q);
         }
-        RIB_STAMP(t, 4);
     }
 }
 
@@ -1126,9 +1080,6 @@ hipError_t launch(const Geo &g, int force_max, const void *q, const void *k, con
         hipError_t e = prepare_kernel((const void *)kern, &cus);
         if (e != hipSuccess) return e;
         int per_cu = NW == 4 ? 2 : 1;               // what LDS and registers allow
-#ifdef RIB_TRACE
-        if (getenv("RIB_PER_CU")) per_cu = atoi(getenv("RIB_PER_CU"));
-#endif
         const int64_t slots = (int64_t)cus * per_cu;
         // (a launch hands a workgroup at most kMaxItemsPerWg items; larger problems take several launches)
         for (int64_t done = 0; done < items;) {
@@ -1166,12 +1117,6 @@ hipError_t launch_pick(const Geo &g, int waves, int force_max, const void *q, co
 
 }  // namespace
 
-#ifdef RIB_TRACE
-extern "C" int rib_debug_read_trace(void *host, size_t bytes)
-{
-    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(rib_trace_buf), bytes);
-}
-#endif
 
 bool mfma_fwd_supported(const Geo &g, int dtype)
 {
@@ -1195,9 +1140,6 @@ static int fast_waves(const Geo &g)
           tokens * g.tstride * 2 < ((int64_t)1 << 32) && small_r))
         return 0;
     if (g.N % 512 != 0) return 4;
-#ifdef RIB_TRACE
-    if (getenv("RIB_FORCE_WAVES")) return atoi(getenv("RIB_FORCE_WAVES"));
-#endif
     if (g.flags & RIB_FLAG_WIDE) return 8;
     const bool ones = g.d < 32, narrow = g.d + g.r <= 48;
     return ones && (narrow || g.N >= 4096) ? 8 : 4;

@@ -674,11 +674,19 @@ __device__ __forceinline__ void clear_pad_columns(const Geo &g, bf16_t *xrow, bf
 
 // Each wave stages its own 64 stationary rows (X rows [64][XS], Y rows [64][YS], extras
 // included) into its private LDS area `W` and reads them back as MFMA B operands.
-template <int DQK, int DVK, bool QDO, bool SCALE, bool XC>
+//
+// MAKE_DELTA (QDO only): the rows' delta_i = dO_i . O_i (paper Sec. 2.2 backward; the softmax Jacobian's row
+// term) is formed here from the dO words the lanes hold anyway plus the matching O words, instead of
+// being read: 16 lanes share a token, each multiplies its channel pair, four DPP steps add the 16
+// partial sums, and a lane permute hands row `lane` its value.  The values are also written to
+// `delta_out` for the dkv kernel, which streams these rows later.  `e1_out` returns the lane's delta.
+template <int DQK, int DVK, bool QDO, bool SCALE, bool XC, bool MAKE_DELTA = false>
 __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u, int n0, const TokMap &tok, const char *xb,
                                                 const char *yb, const bf16_t *f, const float *__restrict__ lse,
                                                 const float *__restrict__ delta, float sc, float sp, bf16_t *W,
-                                                bf16x8 (&Xb)[2][DQK / 16], bf16x8 (&Yb)[2][DVK / 16])
+                                                bf16x8 (&Xb)[2][DQK / 16], bf16x8 (&Yb)[2][DVK / 16],
+                                                const char *ob = nullptr, float *__restrict__ delta_out = nullptr,
+                                                float *e1_out = nullptr)
 {
     using L = Lay<DQK, DVK>;
     const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15, col = lane & 31, hf = lane >> 5;
@@ -689,20 +697,57 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
     const uint32_t tsb = (uint32_t)g.tstride * 2u, ysb = QDO ? (uint32_t)g.C * 2u : tsb, frow = (uint32_t)g.r * 2u;
     const char *fb = (const char *)(f + ((int64_t)hd * g.N + n0) * g.r);
     bf16_t *Xs = W, *Ys = W + kT * L::XS;
-    uint32_t xx[16], yy[16], fa[16], fb2[DQK == 64 ? 16 : 1];
+    uint32_t xx[16], yy[16], fa[16], fb2[DQK == 64 ? 16 : 1], oo[MAKE_DELTA ? 16 : 1];
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
         const int row = p * 4 + sub;
         const uint32_t t = (uint32_t)tok[n0 + row];
         xx[p] = *(const uint32_t *)(xb + (__umul24(t, tsb) + lane_c));
         yy[p] = *(const uint32_t *)(yb + (__umul24(t, ysb) + lane_c));
+        if (MAKE_DELTA) oo[p] = *(const uint32_t *)(ob + (__umul24(t, ysb) + lane_c));
         fa[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f0);
         if (DQK == 64) fb2[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f1);
     }
     float e0 = 0.f, e1 = 0.f;
-    if (QDO && !XC) {
-        e0 = lse[u * g.N + n0 + lane];
-        e1 = delta[u * g.N + n0 + lane];
+    if (QDO && !XC) e0 = lse[u * g.N + n0 + lane];
+    if (QDO && !XC && !MAKE_DELTA) e1 = delta[u * g.N + n0 + lane];
+    if (MAKE_DELTA) {
+        // part[p]: this lane's channel pair of row p*4+sub (lanes past the last pair hold a copy of it and
+        // contribute nothing).  The 16 lanes of a group then reduce and scatter in four halving steps:
+        // a lane keeps the rows whose index bit matches its own lane bit and adds what its partner
+        // (lane ^ 15, ^ 7, ^ 2, ^ 1: all DPP patterns) held for them, so lane j ends with row j*4+sub.
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        float part[16];
+#pragma unroll
+        for (int p = 0; p < 16; ++p)
+            part[p] = j < hp ? __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, yy[p]), __builtin_bit_cast(bf16x2, oo[p]),
+                                                               0.f, false)
+                             : 0.f;
+#define RIB_DPP(x, ctrl) __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (x)), (ctrl), 0xF, 0xF, true))
+        const bool b3 = (j & 8) != 0, b2 = (j & 4) != 0, b1 = (j & 2) != 0, b0 = (j & 1) != 0;
+        float h8[8], h4[4], h2[2];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float keep = b3 ? part[8 + i] : part[i], give = b3 ? part[i] : part[8 + i];
+            h8[i] = keep + RIB_DPP(give, 0x140);        // row_mirror: lane ^ 15
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float keep = b2 ? h8[4 + i] : h8[i], give = b2 ? h8[i] : h8[4 + i];
+            h4[i] = keep + RIB_DPP(give, 0x141);        // row_half_mirror: lane ^ 7
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const float keep = b1 ? h4[2 + i] : h4[i], give = b1 ? h4[i] : h4[2 + i];
+            h2[i] = keep + RIB_DPP(give, 0x4E);         // quad_perm [2,3,0,1]: lane ^ 2
+        }
+        const float keep = b0 ? h2[1] : h2[0], give = b0 ? h2[0] : h2[1];
+        const float mine = keep + RIB_DPP(give, 0xB1);  // quad_perm [1,0,3,2]: lane ^ 1
+#undef RIB_DPP
+        // row `lane` sits in lane (lane & 3) * 16 + (lane >> 2)
+        e1 = __shfl(mine, (lane & 3) * 16 + (lane >> 2));
+        delta_out[u * g.N + n0 + lane] = e1;
+        if (e1_out) *e1_out = e1;
     }
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
@@ -821,8 +866,9 @@ __device__ __forceinline__ void block_coords(const Geo &g, int nblk, int64_t &u,
 template <int DQK, int DVK, int T, int WAVES, bool XC>
 __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_fast_kernel(
     Geo g, int nblk, const bf16_t *__restrict__ q, const bf16_t *__restrict__ k, const bf16_t *__restrict__ v,
-    const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ dout,
-    const float *__restrict__ lse, const float *__restrict__ delta, bf16_t *__restrict__ dq, float *__restrict__ dfq_part)
+    const bf16_t *__restrict__ fq, const bf16_t *__restrict__ fk, const bf16_t *__restrict__ out,
+    const bf16_t *__restrict__ dout, const float *__restrict__ lse, float *__restrict__ delta, bf16_t *__restrict__ dq,
+    float *__restrict__ dfq_part)
 {
     using L = LayT<DQK, DVK, T>;
     using Sm = FSmem<DQK, DVK, T, WAVES>;
@@ -848,8 +894,12 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
 
     const int q0 = (blk * kWaves + wave) * 64;
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
-    stationary_rows<DQK, DVK, true, true, XC>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2, sp2,
-                                    smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb);
+    // (this kernel also makes delta = dO . O for its rows and leaves it in `delta` for the dkv kernel,
+    // which therefore runs after it)
+    float my_delta = 0.f;
+    stationary_rows<DQK, DVK, true, true, XC, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2,
+                                                    sp2, smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb, (const char *)out,
+                                                    delta, &my_delta);
     // LDS is not cleared wholesale.  The padding columns of the streamed row images only ever
     // multiply the zero padding of the stationary operands, but they must be finite for that:
     // they are zeroed once here, in both stages (nothing writes them afterwards).  Unwritten rows
@@ -873,7 +923,7 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
             nl[qb] = kTruncLog2 - lse[u * g.N + q0 + qb * 32 + col] * kLog2e;
-            nd[qb] = -delta[u * g.N + q0 + qb * 32 + col];
+            nd[qb] = -__shfl(my_delta, qb * 32 + col);
         }
     }
 
@@ -1090,8 +1140,8 @@ static bool bwd_fast_ok(const Geo &g)
 // Launch the fast pair with workgroups of WAVES waves and streamed tiles of T tokens.
 template <int DQK, int DVK, int T, int WAVES, bool XC>
 hipError_t launch_fast(const Geo &g, const void *q, const void *k, const void *v, const void *fq, const void *fk,
-                       const void *dout, const float *lse, const float *delta, void *dq, void *dk, void *dv, float *pq,
-                       float *pk, hipStream_t st)
+                       const void *out, const void *dout, const float *lse, float *delta, void *dq, void *dk, void *dv,
+                       float *pq, float *pk, hipStream_t st)
 {
     const size_t smem = FSmem<DQK, DVK, T, WAVES>::BYTES + (size_t)2 * g.M * sizeof(int);
     if (smem > (size_t)kMaxDynLds) return hipErrorInvalidValue;
@@ -1102,13 +1152,15 @@ hipError_t launch_fast(const Geo &g, const void *q, const void *k, const void *v
     if (pe != hipSuccess) return pe;
     const int nblk = g.N / (WAVES * 64);
     const dim3 grid((unsigned)(g.units * nblk)), block(WAVES * 64);
-    hipLaunchKernelGGL(kdkv, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dk,
-                       (bf16_t *)dv, pk);
+    // dq first: it writes the delta rows the dkv kernel streams
+    hipLaunchKernelGGL(kdq, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)out, (const bf16_t *)dout, lse, delta,
+                       (bf16_t *)dq, pq);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kdq, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
-                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, delta, (bf16_t *)dq, pq);
+    hipLaunchKernelGGL(kdkv, grid, block, smem, st, g, nblk, (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v,
+                       (const bf16_t *)fq, (const bf16_t *)fk, (const bf16_t *)dout, lse, (const float *)delta,
+                       (bf16_t *)dk, (bf16_t *)dv, pk);
     return hipGetLastError();
 }
 
@@ -1122,23 +1174,25 @@ hipError_t launch(const Geo &g, const void *q, const void *k, const void *v, con
     float *delta = (float *)((char *)ws + l.delta_off);
     float *pq = (float *)((char *)ws + l.dfq_off);
     float *pk = (float *)((char *)ws + l.dfk_off);
-    hipError_t e = g.gate ? hipSuccess : launch_delta(g, RIB_BF16, out, dout, delta, st);   // (gated: done by the caller)
-    if (e != hipSuccess) return e;
-
+    hipError_t e = hipSuccess;
     if (bwd_fast_ok(g)) {
+        // (delta is made inside the dq kernel; for a gated call the caller's pass over dO', G, O has
+        // written the same values already)
         // Large windows with enough workgroups to go round: 8 waves share each streamed tile (128
         // tokens), which halves the staging work per wave (measured +6..10 % at N = 4096 and 9216).
         // At N = 1024 the single workgroup per CU this implies leaves the per-workgroup prologue
         // and epilogue uncovered and is slower.
         const bool wide = (g.flags & RIB_FLAG_WIDE) != 0 || (g.N >= 4096 && g.units * (g.N / 512) >= 1024);
         if (g.N % 512 == 0 && wide)
-            e = launch_fast<DQK, DVK, 128, 8, XC>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
+            e = launch_fast<DQK, DVK, 128, 8, XC>(g, q, k, v, fq, fk, out, dout, lse, delta, dq, dk, dv, pq, pk, st);
         else
-            e = launch_fast<DQK, DVK, 64, 4, XC>(g, q, k, v, fq, fk, dout, lse, delta, dq, dk, dv, pq, pk, st);
+            e = launch_fast<DQK, DVK, 64, 4, XC>(g, q, k, v, fq, fk, out, dout, lse, delta, dq, dk, dv, pq, pk, st);
         if (e != hipSuccess) return e;
         return launch_reduce_df(g, pq, pk, dfq, dfk, st);
     }
     if constexpr (XC) return hipErrorInvalidValue;   // the general kernels carry the extras in columns only
+    if (!g.gate) e = launch_delta(g, RIB_BF16, out, dout, delta, st);     // (gated: done by the caller)
+    if (e != hipSuccess) return e;
 
     const int ntiles = (g.N + kT - 1) / kT;
     const int nblk = (ntiles + kWaves - 1) / kWaves;

@@ -972,6 +972,58 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
             q_request<DQK>(qr, g, map_at(g, maps + ((t + 1) % 3) * map_words), ni.hd, ni.blk * NT + wave * 64, tsb, q, fq);
         }
 
+        // Two forms of the output stage; which one is faster was measured per variant: the narrow variants
+        // with the ones row (d < 32, d + r <= 48: the benchmark configs, r = 18) store directly (1 % at N = 1024,
+        // 5 % at N = 256), the 64-column and d = 32 variants are 1-4 % faster through the LDS transpose.
+        constexpr bool kDirectStores = ONES && DQK <= 48;
+        if constexpr (kDirectStores) {
+        if (!redo) {
+            // Normalise and store straight from the accumulator layout: a lane holds, for ONE token, four
+            // groups of four consecutive channels (8 bytes each), so a token's head slice leaves as four
+            // 8-byte stores of the two lane halves, back to back.  (Sending O through LDS first, for
+            // stores of whole token rows, took more instructions than the wider rows saved.)
+            const int lane = opaque_tid() & 63, col = lane & 31, hf = lane >> 5;
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                // byte offset of this lane's token slice in a dense [tokens][C] tensor (fits 32 bits, as
+                // every offset on this path does)
+                const uint32_t obase = ((uint32_t)ctok[q0 + qb * 32 + col] * (uint32_t)g.C + (uint32_t)(ci.hd * g.d + 4 * hf)) * 2u;
+                dword2 gw[4];
+                if (g.gate != nullptr) {    // gate words of the channels this lane will store: requested early
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        gw[c4].x = 0u, gw[c4].y = 0u;
+                        const char *gp = (const char *)g.gate + (obase + 16u * c4);
+                        if (8 * c4 + 4 * hf + 4 <= g.d) gw[c4] = *(const dword2 *)gp;
+                        else if (8 * c4 + 4 * hf + 2 <= g.d) gw[c4].x = *(const uint32_t *)gp;
+                    }
+                }
+                const float l = ONES ? ones_row(O[qb], g.d) : lsum[qb] + __shfl_xor(lsum[qb], 32);
+                const float inv = 1.f / l;
+                if (lse != nullptr && hf == 0)
+                    lse[(int64_t)ci.u * g.N + q0 + qb * 32 + col] = (__builtin_amdgcn_logf(l) + (bias ? 0.f : kTruncLog2)) * kLn2;
+#pragma unroll
+                for (int c4 = 0; c4 < 4; ++c4) {
+                    dword2 w2;
+                    w2.x = pack_bf16(O[qb][4 * c4] * inv, O[qb][4 * c4 + 1] * inv);
+                    w2.y = pack_bf16(O[qb][4 * c4 + 2] * inv, O[qb][4 * c4 + 3] * inv);
+                    dword2 wo = w2;
+                    if (g.gate != nullptr) {    // CLA gate (Eq. 9) on the way out, the raw O beside it if asked for
+                        wo.x = pack_bf16(lo_bf16(w2.x) * lo_bf16(gw[c4].x), hi_bf16(w2.x) * hi_bf16(gw[c4].x));
+                        wo.y = pack_bf16(lo_bf16(w2.y) * lo_bf16(gw[c4].y), hi_bf16(w2.y) * hi_bf16(gw[c4].y));
+                    }
+                    const uint32_t off = obase + 16u * c4;
+                    if (8 * c4 + 4 * hf + 4 <= g.d) {
+                        *(dword2 *)((char *)out + off) = wo;
+                        if (g.gate != nullptr && g.out_raw) *(dword2 *)((char *)g.out_raw + off) = w2;
+                    } else if (8 * c4 + 4 * hf + 2 <= g.d) {
+                        *(uint32_t *)((char *)out + off) = wo.x;
+                        if (g.gate != nullptr && g.out_raw) *(uint32_t *)((char *)g.out_raw + off) = w2.x;
+                    }
+                }
+            }
+        }
+        } else {
         if (!redo) {
             // Normalise, then send O through LDS so that the global stores are token rows: in the
             // accumulator layout a lane holds 16 channels of ONE token, and storing from there would
@@ -1016,6 +1068,7 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
                 }
                 __builtin_amdgcn_wave_barrier();
             }
+        }
         }
 
         if (t + 1 < my_n) {

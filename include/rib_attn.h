@@ -69,7 +69,9 @@ typedef enum {
     RIB_ERR_DTYPE = 3,       /* dtype is not one of rib_dtype */
     RIB_ERR_UNSUPPORTED = 4, /* valid problem, but d / r beyond what the kernels are built for */
     RIB_ERR_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than rib_window_attn_bwd_workspace_bytes */
-    RIB_ERR_LAUNCH = 6       /* HIP reported an error when a kernel was enqueued */
+    RIB_ERR_LAUNCH = 6       /* HIP reported an error when a kernel was enqueued.  The library reads (and thereby
+                                clears) the calling thread's last HIP error after each launch, so an error that
+                                an earlier HIP call of the caller left pending is reported here as well */
 } rib_status;
 
 typedef enum {

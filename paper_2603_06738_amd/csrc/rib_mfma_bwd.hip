@@ -800,9 +800,19 @@ __device__ __forceinline__ void stash_block(const f32x16 &acc, int mb, int hf, f
     for (int i = 0; i < 16; ++i) arow[32 * mb + 8 * (i >> 2) + 4 * hf + (i & 3)] = acc[i];
 }
 
-// columns [0, d) of rows [n0, n0+64) -> a grid tensor (bf16), times `scale`
-__device__ __forceinline__ void flush_rows(const float *As, float scale, bf16_t *__restrict__ dst, const TokMap &tok, int n0,
-                                           int hd, const Geo &g)
+// Byte offsets, in a dense [tokens][C] grid tensor, of the channel pair this lane stores for each of its 16
+// rows (rows p*4 + sub of the wave's 64, pair j of head hd).  They fit 32 bits on this path.
+__device__ __forceinline__ void row_offsets(uint32_t (&off)[16], const TokMap &tok, int n0, int hd, const Geo &g)
+{
+    const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
+    const uint32_t chan = (uint32_t)(hd * g.d + 2 * j) * 2u, row_bytes = (uint32_t)g.C * 2u;
+#pragma unroll
+    for (int p = 0; p < 16; ++p) off[p] = (uint32_t)tok[n0 + p * 4 + sub] * row_bytes + chan;
+}
+
+// columns [0, d) of the wave's 64 rows -> a grid tensor (bf16), times `scale`
+__device__ __forceinline__ void flush_rows(const float *As, float scale, bf16_t *__restrict__ dst, const uint32_t (&off)[16],
+                                           const Geo &g)
 {
     const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15;
     if (2 * j < g.d) {
@@ -810,22 +820,24 @@ __device__ __forceinline__ void flush_rows(const float *As, float scale, bf16_t 
         for (int p = 0; p < 16; ++p) {
             const int row = p * 4 + sub;
             const float a = As[row * kARS + 2 * j] * scale, b = As[row * kARS + 2 * j + 1] * scale;
-            *(uint32_t *)(dst + (int64_t)tok[n0 + row] * g.C + hd * g.d + 2 * j) = pack_bf16(a, b);
+            *(uint32_t *)((char *)dst + off[p]) = pack_bf16(a, b);
         }
     }
 }
 
-// columns [d, d+r) of rows [n0, n0+64) -> this unit's RIB partial (contiguous in memory), times `scale`
+// columns [d, d+r) of the wave's 64 rows -> this unit's RIB partial (contiguous in memory), times `scale`.
+// 16 columns per pass; the branches on r are uniform, only a rank under 16 needs a lane predicate.
 __device__ __forceinline__ void flush_partial(const float *As, float scale, float *__restrict__ part, const Geo &g)
 {
     const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15, r = g.r;
     const float *Fs = As + g.d;
+    for (int c0 = 0; c0 < r; c0 += 16) {
+        const bool whole = c0 + 16 <= r;
 #pragma unroll
-    for (int p = 0; p < 16; ++p) {
-        const int row = p * 4 + sub;
-        if (j < r) part[row * r + j] = Fs[row * kARS + j] * scale;
-        if (16 + j < r) part[row * r + 16 + j] = Fs[row * kARS + 16 + j] * scale;
-        if (32 + j < r) part[row * r + 32 + j] = Fs[row * kARS + 32 + j] * scale;
+        for (int p = 0; p < 16; ++p) {
+            const int row = p * 4 + sub;
+            if (whole || c0 + j < r) part[row * r + c0 + j] = Fs[row * kARS + c0 + j] * scale;
+        }
     }
 }
 
@@ -977,7 +989,9 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) stash_block(acc[qb][mb], mb, hf, As + (qb * 32 + col) * kARS);
     __builtin_amdgcn_wave_barrier();
-    flush_rows(As, g.scale_c, dq, tok, q0, hd, g);
+    uint32_t roff[16];
+    row_offsets(roff, tok, q0, hd, g);
+    flush_rows(As, g.scale_c, dq, roff, g);
     flush_partial(As, g.scale_p, dfq_part + (u * g.N + q0) * g.r, g);
 }
 
@@ -1121,13 +1135,15 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dkv_
         for (int mb = 0; mb < 2; ++mb) stash_block(accK[kb][mb], mb, hf, As + (kb * 32 + col) * kARS);
     __builtin_amdgcn_wave_barrier();
     // (the streamed Q_aug rows carry scale * log2 e: undo the log2 e here)
-    flush_rows(As, kLn2, dk, tok, k0, hd, g);
+    uint32_t roff[16];
+    row_offsets(roff, tok, k0, hd, g);
+    flush_rows(As, kLn2, dk, roff, g);
     flush_partial(As, kLn2, dfk_part + (u * g.N + k0) * g.r, g);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) stash_block(accV[kb], 0, hf, As + (kb * 32 + col) * kARS);
     __builtin_amdgcn_wave_barrier();
-    flush_rows(As, 1.f, dv, tok, k0, hd, g);
+    flush_rows(As, 1.f, dv, roff, g);
 }
 
 static bool bwd_fast_ok(const Geo &g)

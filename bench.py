@@ -31,8 +31,10 @@ PEAK_HBM_GBS = 8000.0
 # scaled by a plain copy of known size).  Where such a run of this very workload is committed under profiles/,
 # its figure is quoted in `traffic_from_profile` with the file it comes from; `traffic` itself stays null.
 PROFILED_TRAFFIC = {
-    "c5": {"forward": {"bytes": 230.6e6, "source": "profiles/c5_step_hbm_traffic.md"},
-           "backward": {"bytes": 1043.5e6, "source": "profiles/c5_step_hbm_traffic.md"}},
+    "c5": {"forward": {"bytes": 250.5e6, "source": "profiles/c5_step_hbm_traffic.md"},
+           "backward": {"bytes": 1041.0e6, "source": "profiles/c5_step_hbm_traffic.md"},
+           "kernels": {"mfma_fwd_stream_kernel": 250.5e6, "mfma_bwd_dq_fast_kernel": 451.5e6,
+                       "mfma_bwd_dkv_fast_kernel": 475.4e6, "reduce_df_kernel": 114.1e6}},
 }
 
 
@@ -368,6 +370,9 @@ def main():
         res["roofline"] = {"kernel": dominant, "bound": k["bound"], "achieved": k["tflops"], "peak": k["peak"],
                            "unit": "TFLOP/s", "frac": k["frac"], "traffic": None, "algorithmic_flop": k["algorithmic_flop"],
                            "avg_launch_us": k["launch_us"],
+                           "traffic_from_profile": next(({"bytes": b, "source": prof_traffic["forward"]["source"]}
+                                                         for n, b in prof_traffic.get("kernels", {}).items()
+                                                         if dominant.startswith(n)), None),
                            "time_source": "HIP events around the phase on the launch stream (this run), split between the "
                                           "phase's kernels in the proportions of a torch.profiler pass of 20 steps"}
     else:       # no per-kernel times: fall back to the phase that dominates the step

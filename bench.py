@@ -6,7 +6,7 @@
 One "step" is one pass of the whole hot path over one batch of synthetic input:
 forward (gather + RIB concat + scores + online softmax + PV + scatter) followed,
 for the training workload, by the backward pass (delta, dQ/dK/dV, RIB gradient
-reduction).  The default workload is config 5 of the benchmark spec (fwd+bwd, bf16,
+reduction).  The default workload is the training-step configuration (config 5: fwd+bwd, bf16,
 B=16, 96x96 grid, 32x32 windows, shift 16).  Inputs are resident in HBM before
 the timed region starts.  Prints ONE JSON line.
 

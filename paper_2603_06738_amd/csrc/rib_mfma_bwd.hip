@@ -680,13 +680,15 @@ __device__ __forceinline__ void clear_pad_columns(const Geo &g, bf16_t *xrow, bf
 // being read: 16 lanes share a token, each multiplies its channel pair, four DPP steps add the 16
 // partial sums, and a lane permute hands row `lane` its value.  The values are also written to
 // `delta_out` for the dkv kernel, which streams these rows later.  `e1_out` returns the lane's delta.
+// `from_o` false (uniform): an earlier pass has made delta already (the gated backward's pass over dO', G, O)
+// and it is read instead.
 template <int DQK, int DVK, bool QDO, bool SCALE, bool XC, bool MAKE_DELTA = false>
 __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u, int n0, const TokMap &tok, const char *xb,
                                                 const char *yb, const bf16_t *f, const float *__restrict__ lse,
                                                 const float *__restrict__ delta, float sc, float sp, bf16_t *W,
                                                 bf16x8 (&Xb)[2][DQK / 16], bf16x8 (&Yb)[2][DVK / 16],
                                                 const char *ob = nullptr, float *__restrict__ delta_out = nullptr,
-                                                float *e1_out = nullptr)
+                                                float *e1_out = nullptr, bool from_o = true)
 {
     using L = Lay<DQK, DVK>;
     const int lane = threadIdx.x & 63, sub = lane >> 4, j = lane & 15, col = lane & 31, hf = lane >> 5;
@@ -704,14 +706,15 @@ __device__ __forceinline__ void stationary_rows(const Geo &g, int hd, int64_t u,
         const uint32_t t = (uint32_t)tok[n0 + row];
         xx[p] = *(const uint32_t *)(xb + (__umul24(t, tsb) + lane_c));
         yy[p] = *(const uint32_t *)(yb + (__umul24(t, ysb) + lane_c));
-        if (MAKE_DELTA) oo[p] = *(const uint32_t *)(ob + (__umul24(t, ysb) + lane_c));
+        if (MAKE_DELTA && from_o) oo[p] = *(const uint32_t *)(ob + (__umul24(t, ysb) + lane_c));
         fa[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f0);
         if (DQK == 64) fb2[p] = *(const uint32_t *)(fb + (uint32_t)row * frow + 4 * f1);
     }
     float e0 = 0.f, e1 = 0.f;
     if (QDO && !XC) e0 = lse[u * g.N + n0 + lane];
-    if (QDO && !XC && !MAKE_DELTA) e1 = delta[u * g.N + n0 + lane];
-    if (MAKE_DELTA) {
+    if (QDO && ((!MAKE_DELTA && !XC) || (MAKE_DELTA && !from_o))) e1 = delta[u * g.N + n0 + lane];   // (made by an earlier pass)
+    if (MAKE_DELTA && !from_o && e1_out) *e1_out = e1;
+    if (MAKE_DELTA && from_o) {
         // part[p]: this lane's channel pair of row p*4+sub (lanes past the last pair hold a copy of it and
         // contribute nothing).  The 16 lanes of a group then reduce and scatter in four halving steps:
         // a lane keeps the rows whose index bit matches its own lane bit and adds what its partner
@@ -907,11 +910,11 @@ __global__ __launch_bounds__(WAVES * 64, (DVK == 32) ? 2 : 1) void mfma_bwd_dq_f
     const int q0 = (blk * kWaves + wave) * 64;
     bf16x8 Qb[2][L::KS], Gb[2][L::VS];
     // (this kernel also makes delta = dO . O for its rows and leaves it in `delta` for the dkv kernel,
-    // which therefore runs after it)
+    // which therefore runs after it; a gated call has it from its pass over dO', G and O already)
     float my_delta = 0.f;
     stationary_rows<DQK, DVK, true, true, XC, true>(g, hd, u, q0, tok, (const char *)q, (const char *)dout, fq, lse, delta, sc2,
                                                     sp2, smem + wave * (64 * L::XS + 64 * L::YS), Qb, Gb, (const char *)out,
-                                                    delta, &my_delta);
+                                                    delta, &my_delta, g.gate == nullptr);
     // LDS is not cleared wholesale.  The padding columns of the streamed row images only ever
     // multiply the zero padding of the stationary operands, but they must be finite for that:
     // they are zeroed once here, in both stages (nothing writes them afterwards).  Unwritten rows

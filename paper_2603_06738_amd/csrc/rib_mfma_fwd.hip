@@ -789,10 +789,13 @@ __device__ __forceinline__ TokMap map_at(const Geo &g, const int *slot)
 
 
 
-// Raw q / f_q words of a wave's 64 query rows: 16 lanes per token, 4 tokens per pass.
+// Raw q / f_q words of a wave's 64 query rows, between their request and their staging.  Two layouts
+// share the registers: the general one (16 lanes per token, 4 tokens per pass: w[p] content pair, w[16 + p]
+// and w[32 + p] RIB pairs of row p*4 + sub) and the direct one (the lane's own two query columns in operand
+// order: w[(qb * KS + t) * 4 + i] = dword i of k-step t).
 template <int DQK>
 struct QRaw {
-    uint32_t qx[16], qa[16], qb[DQK == 64 ? 16 : 1];
+    uint32_t w[DQK == 64 ? 48 : 32];
 };
 template <int DQK>
 __device__ __forceinline__ void q_request(QRaw<DQK> &r, const Geo &g, const TokMap &tok, int hd, int q0, uint32_t tsb,
@@ -807,10 +810,10 @@ __device__ __forceinline__ void q_request(QRaw<DQK> &r, const Geo &g, const TokM
     for (int p = 0; p < 16; ++p) {
         const int row = p * 4 + sub;
         const uint32_t off = __umul24((uint32_t)tok[q0 + row], tsb) + (uint32_t)(hd * g.d + 2 * pair) * 2u;
-        r.qx[p] = *(const uint32_t *)(qbase + off);
+        r.w[p] = *(const uint32_t *)(qbase + off);
         const uint32_t frow = (uint32_t)row * (uint32_t)(g.r * 2);
-        r.qa[p] = *(const uint32_t *)(fqb + frow + 4 * f0);
-        if (DQK == 64) r.qb[p] = *(const uint32_t *)(fqb + frow + 4 * f1);
+        r.w[16 + p] = *(const uint32_t *)(fqb + frow + 4 * f0);
+        if (DQK == 64) r.w[32 + p] = *(const uint32_t *)(fqb + frow + 4 * f1);
     }
 }
 // Scale (Eq. 5, times log2 e), round to bf16 and turn the rows into the B operands of the score
@@ -834,16 +837,90 @@ __device__ __forceinline__ void q_stage(const QRaw<DQK> &r, const Geo &g, bf16_t
         for (int pp = 0; pp < 8; ++pp) {
             const int p = ps * 8 + pp, row = pp * 4 + sub;
             // (column order of the pipelined path: RIB part first, as in its K_aug rows)
-            *(uint32_t *)(Ws + row * KSTR + g.r + 2 * pair) = pack_bf16(lo_bf16(r.qx[p]) * sc, hi_bf16(r.qx[p]) * sc);
-            *(uint32_t *)(Ws + row * KSTR + 2 * f0) = pack_bf16(lo_bf16(r.qa[p]) * sp, hi_bf16(r.qa[p]) * sp);
+            *(uint32_t *)(Ws + row * KSTR + g.r + 2 * pair) = pack_bf16(lo_bf16(r.w[p]) * sc, hi_bf16(r.w[p]) * sc);
+            *(uint32_t *)(Ws + row * KSTR + 2 * f0) = pack_bf16(lo_bf16(r.w[16 + p]) * sp, hi_bf16(r.w[16 + p]) * sp);
             if (DQK == 64)
-                *(uint32_t *)(Ws + row * KSTR + 2 * f1) = pack_bf16(lo_bf16(r.qb[p]) * sp, hi_bf16(r.qb[p]) * sp);
+                *(uint32_t *)(Ws + row * KSTR + 2 * f1) = pack_bf16(lo_bf16(r.w[32 + p]) * sp, hi_bf16(r.w[32 + p]) * sp);
         }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int t = 0; t < KS; ++t) Q[ps][t] = *(const bf16x8 *)(Ws + col * KSTR + 16 * t + 8 * hf);
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+// The direct form, for ranks that are multiples of 8: the row [f_q || q || padding] then falls into whole
+// 16-byte pieces of ONE source each, and a lane fetches the pieces of its own two query columns in
+// operand order -- piece 2t + hf of row q0 + 32 qb + col is k-step t of query block qb -- with no trip
+// through LDS: 3 or 4 loads per query block instead of 16 or 24, one token look-up instead of eight.
+// The last content piece may be short (d = 30: 12 bytes); nothing past the head's slice is read.
+struct __attribute__((packed, aligned(4))) dword4 {
+    uint32_t x, y, z, w;
+};
+template <int DQK>
+__device__ __forceinline__ void q_request_direct(QRaw<DQK> &r, const Geo &g, const TokMap &tok, int hd, int q0,
+                                                 uint32_t tsb, const bf16_t *__restrict__ q,
+                                                 const bf16_t *__restrict__ fq)
+{
+    constexpr int KS = DQK / 16;
+    const int lane = opaque_tid() & 63, col = lane & 31, hf = lane >> 5;
+    const int nf = g.r >> 3;                                    // RIB pieces
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+        const int n = q0 + qb * 32 + col;
+        const char *qsrc = (const char *)q + (__umul24((uint32_t)tok[n], tsb) + (uint32_t)(hd * g.d) * 2u);
+        const char *fsrc = (const char *)fq + (uint32_t)(hd * g.N + n) * (uint32_t)(g.r * 2);
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            const int p = 2 * t + hf, base = (qb * KS + t) * 4;
+            r.w[base] = r.w[base + 1] = r.w[base + 2] = r.w[base + 3] = 0u;
+            if (p < nf) {
+                const dword4 x = *(const dword4 *)(fsrc + 16 * p);
+                r.w[base] = x.x, r.w[base + 1] = x.y, r.w[base + 2] = x.z, r.w[base + 3] = x.w;
+            } else {
+                const int e0 = 8 * (p - nf), nd = (g.d - e0) >> 1;      // first content element, dwords left
+                const char *src = qsrc + 2 * e0;
+                if (nd >= 4) {
+                    const dword4 x = *(const dword4 *)src;
+                    r.w[base] = x.x, r.w[base + 1] = x.y, r.w[base + 2] = x.z, r.w[base + 3] = x.w;
+                } else {
+                    if (nd >= 2) {
+                        const dword2 x = *(const dword2 *)src;
+                        r.w[base] = x.x, r.w[base + 1] = x.y;
+                    }
+                    if (nd == 1) r.w[base] = *(const uint32_t *)src;
+                    if (nd == 3) r.w[base + 2] = *(const uint32_t *)(src + 8);
+                }
+            }
+        }
+    }
+}
+template <int DQK>
+__device__ __forceinline__ void q_stage_direct(const QRaw<DQK> &r, const Geo &g, uint32_t padw, bool bias,
+                                               bf16x8 (&Q)[2][DQK / 16])
+{
+    constexpr int KS = DQK / 16;
+    const int hf = (opaque_tid() & 63) >> 5;
+    const int nf = g.r >> 3;
+    const float sc = g.scale_c * kLog2e, sp = g.scale_p * kLog2e;
+    const int eb = g.d + g.r;                                   // the column of the logit offset
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            const int p = 2 * t + hf, base = (qb * KS + t) * 4;
+            const float s = p < nf ? sp : sc;
+            uint4 o;
+            o.x = pack_bf16(lo_bf16(r.w[base]) * s, hi_bf16(r.w[base]) * s);
+            o.y = pack_bf16(lo_bf16(r.w[base + 1]) * s, hi_bf16(r.w[base + 1]) * s);
+            o.z = pack_bf16(lo_bf16(r.w[base + 2]) * s, hi_bf16(r.w[base + 2]) * s);
+            o.w = pack_bf16(lo_bf16(r.w[base + 3]) * s, hi_bf16(r.w[base + 3]) * s);
+            if (bias && p == (eb >> 3)) {       // (d and r even, r a multiple of 8: the column opens a dword)
+                const int dw = (eb & 7) >> 1;
+                o.x = dw == 0 ? padw : o.x, o.y = dw == 1 ? padw : o.y, o.z = dw == 2 ? padw : o.z, o.w = dw == 3 ? padw : o.w;
+            }
+            Q[qb][t] = __builtin_bit_cast(bf16x8, o);
+        }
 }
 
 // The pipelined walk of one workgroup over its items (see the kernel below).
@@ -877,6 +954,10 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
     const bool bias = g.d + g.r < DQK;
     const uint32_t padw = bias ? (uint32_t)narrow_bf16(kTruncLog2) : 0u;
     const uint32_t tsb = (uint32_t)g.tstride * 2u;
+    // Q rows straight into operand order (see q_request_direct) where that measured faster: the 64-column
+    // variants with d = 32 (r = 32: 6 % at N = 2304).  With 48 columns the scattered 16-byte loads take longer to
+    // land than the 16-lanes-per-token requests, and the time between items is waiting, not issuing: 2 % slower.
+    const bool direct = DQK == 64 && !ONES && (g.r & 7) == 0;
     const char *kbase = (const char *)k, *vbase = (const char *)v;
 
     Item ci = decode_item(g, item0, nqblk);
@@ -917,14 +998,16 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
         request(rg);
         advance();
         QRaw<DQK> qr;
-        q_request<DQK>(qr, g, lc.tok, ci.hd, ci.blk * NT + wave * 64, tsb, q, fq);     // (cursor still in item 0)
+        if (direct) q_request_direct<DQK>(qr, g, lc.tok, ci.hd, ci.blk * NT + wave * 64, tsb, q, fq);   // (cursor still in item 0)
+        else q_request<DQK>(qr, g, lc.tok, ci.hd, ci.blk * NT + wave * 64, tsb, q, fq);
         {
             const FastConst<DQK> c0 = fast_const<DQK, WAVES>(g, ci.hd, opaque_tid());
             fast_store<DQK, WAVES>(rg, c0, Kf, Vf);
         }
         request(rg);
         advance();
-        q_stage<DQK>(qr, g, Ws, padw, Q);
+        if (direct) q_stage_direct<DQK>(qr, g, padw, bias, Q);
+        else q_stage<DQK>(qr, g, Ws, padw, Q);
     }
     for (int e = tid; e < my_n; e += NT) redo_flag[e] = 0;
     __syncthreads();
@@ -969,7 +1052,9 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
         Item ni = ci;
         if (t + 1 < my_n) {     // the next item's Q rows are requested now and land during the epilogue
             ni = decode_item(g, item0 + nx * (t + 1), nqblk);
-            q_request<DQK>(qr, g, map_at(g, maps + ((t + 1) % 3) * map_words), ni.hd, ni.blk * NT + wave * 64, tsb, q, fq);
+            const TokMap ntok = map_at(g, maps + ((t + 1) % 3) * map_words);
+            if (direct) q_request_direct<DQK>(qr, g, ntok, ni.hd, ni.blk * NT + wave * 64, tsb, q, fq);
+            else q_request<DQK>(qr, g, ntok, ni.hd, ni.blk * NT + wave * 64, tsb, q, fq);
         }
 
         // Two forms of the output stage; which one is faster was measured per variant: the narrow variants
@@ -1073,7 +1158,8 @@ __device__ __forceinline__ void stream_items(const Geo &g, int nqblk, int item0,
 
         if (t + 1 < my_n) {
             ci = ni;
-            q_stage<DQK>(qr, g, Ws, padw, Q);
+            if (direct) q_stage_direct<DQK>(qr, g, padw, bias, Q);
+            else q_stage<DQK>(qr, g, Ws, padw, Q);
         }
     }
 }

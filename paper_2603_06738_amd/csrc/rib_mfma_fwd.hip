@@ -26,11 +26,12 @@
 //   logit in about +-126, so subtracting the row maximum is only needed for
 //   extreme logits.  The kernel first runs WITHOUT a stabiliser; afterwards every
 //   row checks that its denominator lies in [2^-60, 2^60] (which bounds the largest
-//   term and makes flushed terms negligible).  If any row of the workgroup fails,
-//   or the caller asks for it, the workgroup redoes its queries with a running
-//   maximum that is raised lazily (only when a tile exceeds it by 2^8) and is
-//   subtracted for free as the C operand of the score MFMA.  Both paths compute
-//   the exact softmax up to rounding.
+//   term and makes flushed terms negligible).  An item with a failing row (every
+//   item, if the caller asks for it) is done again with a running maximum that is
+//   raised lazily (only when a tile exceeds it by 2^8) and is subtracted for free
+//   as the C operand of the score MFMA; the streaming kernel notes such items and
+//   redoes them after its last one.  Both paths compute the exact softmax up to
+//   rounding.
 
 #include "rib_common.h"
 
@@ -70,7 +71,8 @@ __device__ __forceinline__ int opaque_tid()
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(const uint4 &w) { return __builtin_bit_cast(bf16x8, w); }
 // Mean relative loss of truncating to bf16 (spacing 2^-7, mantissa log-uniform in [1,2)):
-// 2^-8 / (2 ln 2) * ... = 2^-8 * 0.7213; as a log2 it is added back to the softmax denominator's log.
+// 2^-8 * 0.7213.  As a log2 it is added to every logit before the truncation (a padding column
+// of Q_aug against ones in K_aug) or, where no column is free, to the denominator's log.
 constexpr float kTruncLog2 = 0.0040593f;
 __device__ __forceinline__ float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

@@ -14,6 +14,8 @@
 //     TRANSPOSED blocks S^T, dP^T (a lane owns a QUERY column), so dS^T is the B
 //     operand of dQ_aug^T += K_aug^T dS^T (contraction over keys).
 //
+//   In both kernels it is Q_aug that carries scale * log2(e), rounded to bf16 exactly as the
+//   forward rounds it, so the recomputed logits are the forward's bit for bit.
 //   P is recomputed as exp2(S - LSE) and dS = P (dP - delta).  Neither
 //   subtraction costs a vector instruction: -LSE*log2(e), split into a bf16 high
 //   and low part, rides in the last two padding columns of Q_aug against ones in
@@ -497,7 +499,10 @@ __global__ __launch_bounds__(kNT, (DQK == 48 && DVK == 32) ? 2 : 1) void mfma_bw
 //   - staging has no predicates (idle lanes duplicate a neighbour), builds byte offsets
 //     with one 24-bit multiply-add, and writes the transposed images four tokens at a time;
 //   - P and dS go to bf16 by truncation (one byte-permute per pair instead of the slow
-//     rounding convert); the mean loss of truncation is multiplied back into the results.
+//     rounding convert); the mean loss of truncation is made up beforehand, as an offset on
+//     -LSE*log2(e) (see kTruncLog2);
+//   - the dq kernel makes delta = dO.O for its rows while it stages them and writes it out
+//     for the dkv kernel, which runs second (no separate pass over O and dO).
 // LDS image of one streamed tile of T tokens (same parts as Lay, tile size a parameter).
 template <int DQK, int DVK, int T>
 struct LayT {

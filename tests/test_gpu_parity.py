@@ -40,6 +40,9 @@ def _small_cases():
             c(f"d16r16-{dt}", dt, 1, 16, 16, 3, 16, 16, 16, 0, 215),        # SST-light first cycle
             c(f"d30r18m12-{dt}", dt, 1, 12, 24, 2, 30, 18, 12, 5, 216),     # SST rank on a ragged window
             c(f"d30r34m12-{dt}", dt, 1, 12, 12, 2, 30, 34, 12, 0, 217),
+            c(f"d32r24-{dt}", dt, 1, 16, 32, 2, 32, 24, 16, 3, 218),        # d = 32, an odd number of 16-byte RIB pieces
+            c(f"d28r24-{dt}", dt, 1, 16, 16, 2, 28, 24, 16, 0, 219),        # 64 columns with the ones row
+            c(f"d4r4-{dt}", dt, 1, 16, 16, 2, 4, 4, 16, 1, 220),            # the smallest head the streaming kernels take
         ]
     return cases
 

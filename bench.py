@@ -29,7 +29,7 @@ PEAK_F32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 MFMA, vendor figure
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch are NOT measured by this script (that takes rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # scaled by a plain copy of known size).  Where such a run of this very workload is committed under profiles/,
-# its figure is quoted in `traffic_from_profile` with the file it comes from; `traffic` itself stays null.
+# `traffic` carries its figure and `traffic_from_profile` says which file it comes from; otherwise `traffic` is null.
 PROFILED_TRAFFIC = {
     "c5": {"forward": {"bytes": 250.5e6, "source": "profiles/c5_step_hbm_traffic.md"},
            "backward": {"bytes": 1041.0e6, "source": "profiles/c5_step_hbm_traffic.md"},
@@ -330,7 +330,8 @@ def main():
     peak, bound = family_peak(fam)
     prof_traffic = PROFILED_TRAFFIC.get(wl.name, {})
     res["roofline_fwd"] = {"kernel": "forward (" + fam + "), one launch", "bound": bound, "achieved": round(fwd_tflops, 2),
-                           "peak": peak, "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4), "traffic": None,
+                           "peak": peak, "unit": "TFLOP/s", "frac": round(fwd_tflops / peak, 4),
+                           "traffic": (prof_traffic.get("forward") or {}).get("bytes"),
                            "traffic_from_profile": prof_traffic.get("forward"),
                            "algorithmic_flop": wl.fwd_flop, "algorithmic_bytes": wl.fwd_bytes,
                            "time_source": "HIP events on the launch stream, this run"}
@@ -338,7 +339,8 @@ def main():
         bpeak, bbound = family_peak(rb.kernel_name(r.p, True))
         res["roofline_bwd"] = {"kernel": "backward (" + rb.kernel_name(r.p, True) + "), all its launches",
                                "bound": bbound, "achieved": round(bwd_tflops, 2),
-                               "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4), "traffic": None,
+                               "peak": bpeak, "unit": "TFLOP/s", "frac": round(bwd_tflops / bpeak, 4),
+                               "traffic": (prof_traffic.get("backward") or {}).get("bytes"),
                                "traffic_from_profile": prof_traffic.get("backward"),
                                "algorithmic_flop": wl.bwd_flop, "time_source": "HIP events on the launch stream, this run"}
     kern = {} if a.no_kernel_table else profile_kernels(r)
@@ -368,13 +370,15 @@ def main():
     if dominant is not None and "frac" in rows[dominant]:
         k = rows[dominant]
         res["roofline"] = {"kernel": dominant, "bound": k["bound"], "achieved": k["tflops"], "peak": k["peak"],
-                           "unit": "TFLOP/s", "frac": k["frac"], "traffic": None, "algorithmic_flop": k["algorithmic_flop"],
+                           "unit": "TFLOP/s", "frac": k["frac"], "algorithmic_flop": k["algorithmic_flop"],
                            "avg_launch_us": k["launch_us"],
                            "traffic_from_profile": next(({"bytes": b, "source": prof_traffic["forward"]["source"]}
                                                          for n, b in prof_traffic.get("kernels", {}).items()
                                                          if dominant.startswith(n)), None),
                            "time_source": "HIP events around the phase on the launch stream (this run), split between the "
                                           "phase's kernels in the proportions of a torch.profiler pass of 20 steps"}
+        # HBM bytes per launch: the rocprofv3 FETCH_SIZE / WRITE_SIZE runs under profiles/ (not this run), else null
+        res["roofline"]["traffic"] = (res["roofline"]["traffic_from_profile"] or {}).get("bytes")
     else:       # no per-kernel times: fall back to the phase that dominates the step
         res["roofline"] = dict(res["roofline_bwd"] if wl.backward and bwd_ms > fwd_ms else res["roofline_fwd"])
     # the headline shape of the forward target (config 3, 32x32 windows): a short run of its own
